@@ -1,0 +1,210 @@
+/*
+ * palmdecode.h -- C ABI of the MI355X (gfx950) int8-weight multiquery decode step.
+ *
+ * One generate-phase step of a PaLM-style stack (paper Section 2.2: one forward
+ * pass over B x 1 tokens; Section 3.4: parallel block
+ *     x' = x + Attn(LN(x)) + SwiGLU-FFN(LN(x))
+ * with the input projections fused into one matrix and the two output
+ * projections fused into another; Section 3.3: multiquery attention, all query
+ * heads share one K/V head; Section 3.6: int8 weights, one scale per output
+ * channel, arithmetic in bf16/fp32).
+ *
+ * Conventions
+ *   - Every function returns a pd_status (0 = PD_OK, negative = error) and
+ *     never throws.  pd_last_error() returns a thread-local text for the last
+ *     failure on the calling thread.
+ *   - "device" pointers are HIP device memory owned by the CALLER for the whole
+ *     call (and until the stream has drained); the library allocates no device
+ *     memory.  "host" pointers are ordinary host memory.
+ *   - bf16 values are passed as uint16_t bit patterns.
+ *   - Device pointers must be 16-byte aligned (256 for packed weights, caches
+ *     and workspace).  All argument errors are detected on the host before
+ *     anything is enqueued: on error nothing has been launched.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Calls
+ *     are asynchronous: they return after enqueueing.
+ *
+ * Canonical (caller-side) layouts
+ *   w_in   [d_model][n_in]  int8 row-major, columns q(H*dh) | k(dh) | v(dh) | gate(F) | up(F)
+ *   s_in   [n_in]           bf16, scale of output channel n:  W[k][n] = w_in[k][n] * s_in[n]
+ *   w_out  [k_out][d_model] int8 row-major, rows attention-out(H*dh) | FFN activation(F)
+ *   s_out  [d_model]        bf16
+ *   gamma  [d_model]        bf16 LayerNorm gain (no bias; eps inside the root)
+ *   K, V   [B][L_ctx][d_head] bf16 per layer (K holds rotated keys)
+ *   with n_in = H*dh + 2*dh + 2*F and k_out = H*dh + F.
+ *
+ * Library-side layouts (Section 3.5 lists in-memory tensor layout among the
+ * low-level optimisations; these are this library's, chosen so that every
+ * 64-lane wavefront streams 1 KiB contiguous pieces straight into MFMA operands)
+ *   packed layer  = pd_packed_layer_bytes() bytes made by pd_pack_layer().
+ *   K cache [n_layers][B][L_ctx/32][dh/16][2][32][8] bf16:
+ *       element (l,b,t,c) -> [l][b][t/32][c/16][(c%16)/8][t%32][c%8]
+ *   V cache [n_layers][B][L_ctx/32][dh/32][2][2][32][8] bf16:
+ *       element (l,b,t,c) -> [l][b][t/32][c/32][(t%32)/16][(t%8)/4][c%32][4*((t%16)/8) + t%4]
+ *   L_ctx must be a multiple of 32.  pd_kv_import()/pd_kv_export() convert one
+ *   layer between canonical and library layout.
+ */
+#ifndef PALMDECODE_H
+#define PALMDECODE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int32_t pd_status;
+enum {
+    PD_OK = 0,
+    PD_ERR_NULL = -1,      /* a required pointer is NULL */
+    PD_ERR_ALIGN = -2,     /* a device pointer is not aligned as required */
+    PD_ERR_SHAPE = -3,     /* model shape / batch / context not supported */
+    PD_ERR_RANGE = -4,     /* an index argument is out of range */
+    PD_ERR_WORKSPACE = -5, /* workspace_bytes smaller than pd_workspace_bytes() */
+    PD_ERR_HIP = -6,       /* a HIP runtime call failed */
+    PD_ERR_POSITION = -7,  /* a device-side positions[b] was outside [0, L_ctx) */
+    PD_ERR_STATE = -8      /* call not valid in the handle's current state */
+};
+
+/* Model description (Section 2.2 notation: d_model = E, d_ff = F, n_heads = H).
+ * Supported: d_model % 128 == 0, (H*d_head + d_ff) % 128 == 0, d_ff % 32 == 0,
+ * d_head in {64, 128, 256}, 1 <= n_heads <= 32, n_kv_heads == 1. */
+typedef struct pd_model_desc {
+    int32_t n_layers;
+    int32_t d_model;
+    int32_t n_heads;
+    int32_t d_head;
+    int32_t d_ff;       /* per SwiGLU branch */
+    int32_t n_kv_heads; /* must be 1 (multiquery, Section 3.3) */
+    float rope_base;    /* 10000 */
+    float ln_eps;       /* 1e-6 */
+    int32_t flags;      /* reserved, 0 */
+} pd_model_desc;
+
+typedef struct pd_handle pd_handle;
+
+const char* pd_status_string(pd_status code);
+const char* pd_last_error(void);
+
+/* ---- sizes: pure host functions ------------------------------------------ */
+
+/* Bytes of one packed layer (int8 matrices, fp32 scales and gain, 256-aligned).
+ * The packed stack is n_layers such blobs back to back. */
+pd_status pd_packed_layer_bytes(const pd_model_desc* desc, size_t* bytes);
+/* Bytes of EACH of the K cache and the V cache for batch B, capacity L_ctx. */
+pd_status pd_kv_cache_bytes(const pd_model_desc* desc, int32_t B, int32_t L_ctx, size_t* bytes);
+/* Scratch a decode call needs for batch B, capacity L_ctx. */
+pd_status pd_workspace_bytes(const pd_model_desc* desc, int32_t B, int32_t L_ctx, size_t* bytes);
+
+/* ---- handle --------------------------------------------------------------- */
+
+/* Validates and copies `desc`.  The handle owns host state only (launch plan,
+ * an optional captured graph). */
+pd_status pd_create(const pd_model_desc* desc, pd_handle** out);
+pd_status pd_destroy(pd_handle* h);
+/* Tuning knobs, e.g. "split_in", "split_out" (K-splits of the two projections,
+ * 0 = automatic), "attn_blocks_per_split" (32-token blocks per attention
+ * workgroup, 0 = automatic).  Unknown names return PD_ERR_RANGE. */
+pd_status pd_set_option(pd_handle* h, const char* name, int32_t value);
+
+/* Event timing of one kernel class, for the roofline report.  Option
+ * "profile_kernel" = 1 (input projection), 2 (attention + combine), 3 (output
+ * projection), 4 (input epilogue), 5 (output epilogue), 0 = off: while on, every
+ * launch of that class made by pd_decode_step/pd_decode_layer is bracketed by
+ * HIP events on the caller's stream.  pd_profile_read() waits for them, returns
+ * the summed duration and the number of launches, and resets the counters. */
+pd_status pd_profile_read(pd_handle* h, double* total_ms, int32_t* launches);
+
+/* ---- data preparation ----------------------------------------------------- */
+
+/* Re-tiles one layer's canonical device tensors into the packed blob at
+ * `packed_layer` (device, 256-aligned, pd_packed_layer_bytes() bytes).  The
+ * canonical buffers may be freed once the stream has drained.  Section 3.5
+ * (tensor layouts chosen to avoid padding and copies in the matrix multiplies). */
+pd_status pd_pack_layer(pd_handle* h, const int8_t* w_in, const uint16_t* s_in,
+                        const int8_t* w_out, const uint16_t* s_out, const uint16_t* gamma,
+                        void* packed_layer, void* stream);
+
+/* Generic pieces of the same packing for a single [K][N] int8 matrix (K % 128
+ * == 0, N % 32 == 0): packed_w gets K*N bytes. */
+pd_status pd_pack_matrix(const int8_t* w, int32_t K, int32_t N, void* packed_w, void* stream);
+
+/* One layer of the cache, canonical [B][L_ctx][dh] <-> library layout, at layer
+ * index `layer` of the library-side K or V cache (`is_v` selects the V layout). */
+pd_status pd_kv_import(pd_handle* h, const uint16_t* canonical, void* cache, int32_t layer,
+                       int32_t B, int32_t L_ctx, int32_t is_v, void* stream);
+pd_status pd_kv_export(pd_handle* h, const void* cache, uint16_t* canonical, int32_t layer,
+                       int32_t B, int32_t L_ctx, int32_t is_v, void* stream);
+
+/* ---- the hot path --------------------------------------------------------- */
+
+/*
+ * One decode step of the whole stack (Section 2.2; Section 3.4 block).
+ *   packed_weights  device, n_layers packed layers back to back
+ *   k_cache,v_cache device, library layout, in/out: for every layer l and
+ *                   sequence b exactly slot (l, b, positions[b]) is written
+ *                   (rotated key / value of this token, rounded to bf16) and
+ *                   slots 0..positions[b] are read; nothing else is touched
+ *   x_in            device [B][d_model] bf16
+ *   positions       device [B] int32, index of the token being decoded
+ *   x_out           device [B][d_model] bf16 (may alias x_in): hidden state after
+ *                   the last block; the residual stream is fp32 inside the call
+ *   workspace       device, >= pd_workspace_bytes(desc, B, L_ctx)
+ * A positions[b] outside [0, L_ctx) is device data the host cannot see: that
+ * row writes nothing to the cache, its x_out row is unspecified, and a flag is
+ * raised in the workspace that pd_check_async() reports.
+ */
+pd_status pd_decode_step(pd_handle* h, const void* packed_weights, void* k_cache, void* v_cache,
+                         const uint16_t* x_in, const int32_t* positions, int32_t B, int32_t L_ctx,
+                         uint16_t* x_out, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * One layer of the step, for per-layer checks and for a weight shard's
+ * unreduced partial (Section 3.2.1: a 1D weight-stationary shard over heads
+ * and d_ff produces a partial sum that still needs a cross-chip reduction).
+ *   layer         index into the caches (the packed blob is passed directly)
+ *   y_out         device [B][d_model] fp32: x + block(x) if add_residual != 0,
+ *                 else block(x) alone
+ */
+pd_status pd_decode_layer(pd_handle* h, int32_t layer, const void* packed_layer, void* k_cache,
+                          void* v_cache, const uint16_t* x_in, const int32_t* positions, int32_t B,
+                          int32_t L_ctx, float* y_out, int32_t add_residual, void* workspace,
+                          size_t workspace_bytes, void* stream);
+
+/* Synchronises `stream`, then reports the per-row position flags the most
+ * recent step on this `workspace` left: PD_OK or PD_ERR_POSITION. */
+pd_status pd_check_async(pd_handle* h, void* workspace, void* stream);
+
+/* ---- single steps of the path (tests, profiling) -------------------------- */
+
+/* out[b][n] = s[n] * sum_k a[b][k] * w[k][n]   (Section 3.6 weight-only int8)
+ *   packed_w from pd_pack_matrix, scale [N] fp32 device, a [B][K] bf16 device,
+ *   out [B][N] fp32 device, B <= 256.  workspace >= pd_qgemm_workspace_bytes(). */
+pd_status pd_qgemm_workspace_bytes(int32_t B, int32_t K, int32_t N, size_t* bytes);
+pd_status pd_qgemm(const void* packed_w, const float* scale, const uint16_t* a, int32_t B,
+                   int32_t K, int32_t N, float* out, int32_t k_splits, void* workspace,
+                   size_t workspace_bytes, void* stream);
+
+/* Multiquery attention of one layer over the library-layout cache (Section 3.3):
+ *   q [B][H][dh] bf16 (already rotated), o [B][H*dh] bf16,
+ *   attends over slots 0..positions[b] of layer `layer`. */
+pd_status pd_mqa_attend(pd_handle* h, int32_t layer, const uint16_t* q, const void* k_cache,
+                        const void* v_cache, const int32_t* positions, int32_t B, int32_t L_ctx,
+                        uint16_t* o, void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---- graph replay --------------------------------------------------------- */
+
+/* Captures pd_decode_step(...) with these arguments into a HIP graph owned by
+ * the handle; pd_graph_replay() launches it.  Valid while every pointer, B and
+ * L_ctx stay the same; the CONTENTS of positions, x_in and the caches may change
+ * between replays. */
+pd_status pd_graph_capture(pd_handle* h, const void* packed_weights, void* k_cache, void* v_cache,
+                           const uint16_t* x_in, const int32_t* positions, int32_t B, int32_t L_ctx,
+                           uint16_t* x_out, void* workspace, size_t workspace_bytes, void* stream);
+pd_status pd_graph_replay(pd_handle* h, void* stream);
+pd_status pd_graph_release(pd_handle* h);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PALMDECODE_H */

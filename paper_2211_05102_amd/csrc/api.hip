@@ -1,0 +1,516 @@
+// C ABI of the decode library: argument validation, workspace carving, the
+// layer-stack driver (paper Section 2.2: one forward pass over B x 1 tokens that
+// streams every weight and every live cache slot once) and graph capture.
+#include <hip/hip_runtime.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+#include <vector>
+
+#include "../../include/palmdecode.h"
+#include "kernels.h"
+
+namespace {
+
+thread_local char g_err[256] = "";
+
+pd_status fail(pd_status code, const char* msg) {
+    snprintf(g_err, sizeof(g_err), "%s", msg);
+    return code;
+}
+pd_status fail_hip(hipError_t e, const char* where) {
+    snprintf(g_err, sizeof(g_err), "%s: %s", where, hipGetErrorString(e));
+    return PD_ERR_HIP;
+}
+
+inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+struct Shape {
+    int L, d, H, dh, F, n_qkv, n_in, k_out;
+};
+
+pd_status check_desc(const pd_model_desc* m, Shape* s) {
+    if (!m) return fail(PD_ERR_NULL, "desc is NULL");
+    if (m->n_layers < 1 || m->d_model < 128 || m->d_model % 128) return fail(PD_ERR_SHAPE, "d_model must be a positive multiple of 128, n_layers >= 1");
+    if (m->d_head != 64 && m->d_head != 128 && m->d_head != 256) return fail(PD_ERR_SHAPE, "d_head must be 64, 128 or 256");
+    if (m->n_heads < 1 || m->n_heads > 32) return fail(PD_ERR_SHAPE, "n_heads must be in 1..32");
+    if (m->n_kv_heads != 1) return fail(PD_ERR_SHAPE, "n_kv_heads must be 1 (multiquery)");
+    if (m->d_ff < 32 || m->d_ff % 32) return fail(PD_ERR_SHAPE, "d_ff must be a positive multiple of 32");
+    long long k_out = (long long)m->n_heads * m->d_head + m->d_ff;
+    if (k_out % 128) return fail(PD_ERR_SHAPE, "n_heads*d_head + d_ff must be a multiple of 128");
+    long long n_in = (long long)m->n_heads * m->d_head + 2LL * m->d_head + 2LL * m->d_ff;
+    if (n_in > (1 << 24) || k_out > (1 << 24) || m->d_model > (1 << 20)) return fail(PD_ERR_SHAPE, "model too large");
+    if (!(m->rope_base > 1.0f) || !(m->ln_eps > 0.0f)) return fail(PD_ERR_SHAPE, "rope_base must exceed 1 and ln_eps must be positive");
+    if (s) {
+        s->L = m->n_layers; s->d = m->d_model; s->H = m->n_heads; s->dh = m->d_head; s->F = m->d_ff;
+        s->n_qkv = m->n_heads * m->d_head + 2 * m->d_head;
+        s->n_in = (int)n_in; s->k_out = (int)k_out;
+    }
+    return PD_OK;
+}
+
+pd_status check_batch(int32_t B, int32_t L_ctx) {
+    if (B < 1 || B > 256) return fail(PD_ERR_SHAPE, "B must be in 1..256");
+    if (L_ctx < 32 || L_ctx % 32 || L_ctx > (1 << 20)) return fail(PD_ERR_SHAPE, "L_ctx must be a positive multiple of 32");
+    return PD_OK;
+}
+
+// offsets inside one packed layer
+struct PackedLayout {
+    size_t w_in, w_out, s_in, s_out, gamma, total;
+};
+PackedLayout packed_layout(const Shape& s) {
+    PackedLayout p;
+    size_t o = 0;
+    p.w_in = o; o += align256((size_t)s.d * s.n_in);
+    p.w_out = o; o += align256((size_t)s.k_out * s.d);
+    p.s_in = o; o += align256((size_t)s.n_in * 4);
+    p.s_out = o; o += align256((size_t)s.d * 4);
+    p.gamma = o; o += align256((size_t)s.d * 4);
+    p.total = o;
+    return p;
+}
+
+int auto_bps(int B, int L_ctx) {
+    long long v = (long long)(L_ctx / 32) * B / 512;
+    if (v < PD_MIN_BLOCKS_PER_SPLIT) v = PD_MIN_BLOCKS_PER_SPLIT;
+    if (v > 64) v = 64;
+    return (int)v;
+}
+
+// workspace carving; sized for the largest split counts so options never overflow it
+struct Workspace {
+    size_t flag, cs, xres, h, part_in, q, act, opart, ml, part_out, total;
+};
+Workspace workspace_layout(const Shape& s, int B, int L_ctx) {
+    Workspace w;
+    size_t o = 0;
+    const size_t nsplit_max = (size_t)(L_ctx / 32 + PD_MIN_BLOCKS_PER_SPLIT - 1) / PD_MIN_BLOCKS_PER_SPLIT;
+    w.flag = o; o += 1024;  // 256 per-row position flags
+    w.cs = o; o += align256((size_t)B * (s.dh / 2) * 2 * 4);
+    w.xres = o; o += align256((size_t)B * s.d * 4);
+    w.h = o; o += align256((size_t)B * s.d * 2);
+    w.part_in = o; o += align256((size_t)PD_MAX_SPLITS * B * s.n_in * 4);
+    w.q = o; o += align256((size_t)B * s.H * s.dh * 2);
+    w.act = o; o += align256((size_t)B * s.k_out * 2);
+    w.opart = o; o += align256((size_t)B * nsplit_max * s.H * s.dh * 4);
+    w.ml = o; o += align256((size_t)B * nsplit_max * s.H * 2 * 4);
+    w.part_out = o; o += align256((size_t)PD_MAX_SPLITS * B * s.d * 4);
+    w.total = o;
+    return w;
+}
+
+size_t kv_layer_elems(const Shape& s, int B, int L_ctx) { return (size_t)B * L_ctx * s.dh; }
+
+}  // namespace
+
+struct pd_handle {
+    pd_model_desc desc;
+    Shape s;
+    int opt_split_in = 0, opt_split_out = 0, opt_bps = 0;
+    hipGraph_t graph = nullptr;
+    hipGraphExec_t graph_exec = nullptr;
+    // optional event timing of one kernel class (0 = off), see pd_profile_read
+    int profile_kernel = 0;
+    std::vector<hipEvent_t> ev_pool;  // pairs: start, stop
+    size_t ev_used = 0;
+};
+
+namespace {
+
+#define PD_TRY_HIP(expr, where)                          \
+    do {                                                 \
+        hipError_t _e = (expr);                          \
+        if (_e != hipSuccess) return fail_hip(_e, where); \
+    } while (0)
+
+enum { PROF_QGEMM_IN = 1, PROF_ATTEND = 2, PROF_QGEMM_OUT = 3, PROF_EPI_IN = 4, PROF_EPI_OUT = 5 };
+
+// Records an event on `st` if kernel class `which` is being timed.  Events are
+// created on first use and reused after pd_profile_read().
+void prof_mark(pd_handle* h, int which, hipStream_t st) {
+    if (h->profile_kernel != which) return;
+    if (h->ev_used == h->ev_pool.size()) {
+        hipEvent_t e;
+        if (hipEventCreate(&e) != hipSuccess) return;
+        h->ev_pool.push_back(e);
+    }
+    (void)hipEventRecord(h->ev_pool[h->ev_used++], st);
+}
+
+struct StepArgs {
+    const unsigned char* packed;  // first layer to run
+    void* k_cache;
+    void* v_cache;
+    const uint16_t* x_in;
+    const int32_t* positions;
+    int B, L_ctx;
+    uint16_t* x_out_bf16;
+    float* y_out_f32;
+    int add_residual;
+    int layer0, n_run;  // cache layer index of the first layer, number of layers to run
+    unsigned char* ws;
+};
+
+pd_status run_layers(pd_handle* h, const StepArgs& a, hipStream_t st) {
+    const Shape& s = h->s;
+    const PackedLayout pl = packed_layout(s);
+    const Workspace w = workspace_layout(s, a.B, a.L_ctx);
+    const int B = a.B;
+    float* cs = reinterpret_cast<float*>(a.ws + w.cs);
+    int32_t* flag = reinterpret_cast<int32_t*>(a.ws + w.flag);
+    float* xres = reinterpret_cast<float*>(a.ws + w.xres);
+    uint16_t* hbuf = reinterpret_cast<uint16_t*>(a.ws + w.h);
+    float* part_in = reinterpret_cast<float*>(a.ws + w.part_in);
+    uint16_t* q = reinterpret_cast<uint16_t*>(a.ws + w.q);
+    uint16_t* act = reinterpret_cast<uint16_t*>(a.ws + w.act);
+    float* opart = reinterpret_cast<float*>(a.ws + w.opart);
+    float* ml = reinterpret_cast<float*>(a.ws + w.ml);
+    float* part_out = reinterpret_cast<float*>(a.ws + w.part_out);
+
+    const int S_in = h->opt_split_in > 0 ? h->opt_split_in : pd::qgemm_auto_splits(B, s.d, s.n_in);
+    const int S_out = h->opt_split_out > 0 ? h->opt_split_out : pd::qgemm_auto_splits(B, s.k_out, s.d);
+    const int bps = h->opt_bps > 0 ? h->opt_bps : auto_bps(B, a.L_ctx);
+    const size_t kv_layer_bytes = kv_layer_elems(s, B, a.L_ctx) * 2;
+
+    PD_TRY_HIP(pd::launch_prep(a.positions, B, a.L_ctx, s.dh, h->desc.rope_base, cs, flag, st), "prep");
+    for (int i = 0; i < a.n_run; i++) {
+        const unsigned char* L = a.packed + (size_t)i * pl.total;
+        const float* s_in = reinterpret_cast<const float*>(L + pl.s_in);
+        const float* s_out = reinterpret_cast<const float*>(L + pl.s_out);
+        const float* gamma = reinterpret_cast<const float*>(L + pl.gamma);
+        unsigned char* kc = static_cast<unsigned char*>(a.k_cache) + (size_t)(a.layer0 + i) * kv_layer_bytes;
+        unsigned char* vc = static_cast<unsigned char*>(a.v_cache) + (size_t)(a.layer0 + i) * kv_layer_bytes;
+        if (i == 0)
+            PD_TRY_HIP(pd::launch_ln_first(a.x_in, gamma, B, s.d, h->desc.ln_eps, xres, hbuf, st), "ln_first");
+        prof_mark(h, PROF_QGEMM_IN, st);
+        PD_TRY_HIP(pd::launch_qgemm(L + pl.w_in, hbuf, part_in, B, s.d, s.n_in, s.d, S_in, st), "qgemm_in");
+        prof_mark(h, PROF_QGEMM_IN, st);
+        prof_mark(h, PROF_EPI_IN, st);
+        PD_TRY_HIP(pd::launch_epi_in(part_in, S_in, s_in, cs, a.positions, B, s.H, s.dh, s.F, a.L_ctx, q,
+                                     kc, vc, act, s.k_out, st), "epi_in");
+        prof_mark(h, PROF_EPI_IN, st);
+        prof_mark(h, PROF_ATTEND, st);
+        PD_TRY_HIP(pd::launch_mqa_attend(q, kc, vc, a.positions, B, s.H, s.dh, a.L_ctx, bps, opart, ml,
+                                         act, s.k_out, st), "mqa_attend");
+        prof_mark(h, PROF_ATTEND, st);
+        prof_mark(h, PROF_QGEMM_OUT, st);
+        PD_TRY_HIP(pd::launch_qgemm(L + pl.w_out, act, part_out, B, s.k_out, s.d, s.k_out, S_out, st), "qgemm_out");
+        prof_mark(h, PROF_QGEMM_OUT, st);
+        const bool last = i == a.n_run - 1;
+        const float* gamma_next = last ? nullptr : reinterpret_cast<const float*>(L + pl.total + pl.gamma);
+        prof_mark(h, PROF_EPI_OUT, st);
+        PD_TRY_HIP(pd::launch_epi_out(part_out, S_out, s_out, xres, gamma_next, B, s.d, h->desc.ln_eps,
+                                      a.add_residual, hbuf, last ? a.x_out_bf16 : nullptr,
+                                      last ? a.y_out_f32 : nullptr, st), "epi_out");
+        prof_mark(h, PROF_EPI_OUT, st);
+    }
+    return PD_OK;
+}
+
+pd_status check_step_args(pd_handle* h, const void* packed, void* kc, void* vc, const uint16_t* x_in,
+                          const int32_t* positions, int32_t B, int32_t L_ctx, const void* out,
+                          void* ws, size_t ws_bytes) {
+    if (!h) return fail(PD_ERR_NULL, "handle is NULL");
+    if (!packed || !kc || !vc || !x_in || !positions || !out || !ws) return fail(PD_ERR_NULL, "NULL device pointer");
+    pd_status rc = check_batch(B, L_ctx);
+    if (rc != PD_OK) return rc;
+    if (!aligned(packed, 256) || !aligned(kc, 256) || !aligned(vc, 256) || !aligned(ws, 256))
+        return fail(PD_ERR_ALIGN, "packed weights, caches and workspace must be 256-byte aligned");
+    if (!aligned(x_in, 16) || !aligned(out, 16) || !aligned(positions, 4))
+        return fail(PD_ERR_ALIGN, "x_in/x_out must be 16-byte aligned");
+    if (ws_bytes < workspace_layout(h->s, B, L_ctx).total) return fail(PD_ERR_WORKSPACE, "workspace too small");
+    return PD_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* pd_status_string(pd_status code) {
+    switch (code) {
+        case PD_OK: return "ok";
+        case PD_ERR_NULL: return "null pointer";
+        case PD_ERR_ALIGN: return "misaligned pointer";
+        case PD_ERR_SHAPE: return "unsupported shape";
+        case PD_ERR_RANGE: return "argument out of range";
+        case PD_ERR_WORKSPACE: return "workspace too small";
+        case PD_ERR_HIP: return "HIP runtime error";
+        case PD_ERR_POSITION: return "position outside [0, L_ctx)";
+        case PD_ERR_STATE: return "invalid state";
+        default: return "unknown status";
+    }
+}
+
+const char* pd_last_error(void) { return g_err; }
+
+pd_status pd_packed_layer_bytes(const pd_model_desc* desc, size_t* bytes) {
+    Shape s;
+    pd_status rc = check_desc(desc, &s);
+    if (rc != PD_OK) return rc;
+    if (!bytes) return fail(PD_ERR_NULL, "bytes is NULL");
+    *bytes = packed_layout(s).total;
+    return PD_OK;
+}
+
+pd_status pd_kv_cache_bytes(const pd_model_desc* desc, int32_t B, int32_t L_ctx, size_t* bytes) {
+    Shape s;
+    pd_status rc = check_desc(desc, &s);
+    if (rc != PD_OK) return rc;
+    if ((rc = check_batch(B, L_ctx)) != PD_OK) return rc;
+    if (!bytes) return fail(PD_ERR_NULL, "bytes is NULL");
+    *bytes = (size_t)s.L * kv_layer_elems(s, B, L_ctx) * 2;
+    return PD_OK;
+}
+
+pd_status pd_workspace_bytes(const pd_model_desc* desc, int32_t B, int32_t L_ctx, size_t* bytes) {
+    Shape s;
+    pd_status rc = check_desc(desc, &s);
+    if (rc != PD_OK) return rc;
+    if ((rc = check_batch(B, L_ctx)) != PD_OK) return rc;
+    if (!bytes) return fail(PD_ERR_NULL, "bytes is NULL");
+    *bytes = workspace_layout(s, B, L_ctx).total;
+    return PD_OK;
+}
+
+pd_status pd_create(const pd_model_desc* desc, pd_handle** out) {
+    if (!out) return fail(PD_ERR_NULL, "out is NULL");
+    *out = nullptr;
+    Shape s;
+    pd_status rc = check_desc(desc, &s);
+    if (rc != PD_OK) return rc;
+    pd_handle* h = new (std::nothrow) pd_handle();
+    if (!h) return fail(PD_ERR_STATE, "out of host memory");
+    h->desc = *desc;
+    h->s = s;
+    *out = h;
+    return PD_OK;
+}
+
+pd_status pd_graph_release(pd_handle* h) {
+    if (!h) return fail(PD_ERR_NULL, "handle is NULL");
+    if (h->graph_exec) { (void)hipGraphExecDestroy(h->graph_exec); h->graph_exec = nullptr; }
+    if (h->graph) { (void)hipGraphDestroy(h->graph); h->graph = nullptr; }
+    return PD_OK;
+}
+
+pd_status pd_destroy(pd_handle* h) {
+    if (!h) return PD_OK;
+    pd_graph_release(h);
+    for (hipEvent_t e : h->ev_pool) (void)hipEventDestroy(e);
+    delete h;
+    return PD_OK;
+}
+
+pd_status pd_set_option(pd_handle* h, const char* name, int32_t value) {
+    if (!h || !name) return fail(PD_ERR_NULL, "NULL argument");
+    if (!strcmp(name, "split_in") || !strcmp(name, "split_out")) {
+        if (value < 0 || value > PD_MAX_SPLITS) return fail(PD_ERR_RANGE, "split count must be in 0..16");
+        int K = !strcmp(name, "split_in") ? h->s.d : h->s.k_out;
+        if (value > K / 128) return fail(PD_ERR_RANGE, "more splits than 128-row chunks");
+        (!strcmp(name, "split_in") ? h->opt_split_in : h->opt_split_out) = value;
+        return PD_OK;
+    }
+    if (!strcmp(name, "attn_blocks_per_split")) {
+        if (value != 0 && (value < PD_MIN_BLOCKS_PER_SPLIT || value > 4096)) return fail(PD_ERR_RANGE, "attn_blocks_per_split must be 0 or in 4..4096");
+        h->opt_bps = value;
+        return PD_OK;
+    }
+    if (!strcmp(name, "profile_kernel")) {
+        if (value < 0 || value > PROF_EPI_OUT) return fail(PD_ERR_RANGE, "profile_kernel must be in 0..5");
+        h->profile_kernel = value;
+        h->ev_used = 0;
+        return PD_OK;
+    }
+    return fail(PD_ERR_RANGE, "unknown option");
+}
+
+pd_status pd_profile_read(pd_handle* h, double* total_ms, int32_t* launches) {
+    if (!h || !total_ms || !launches) return fail(PD_ERR_NULL, "NULL argument");
+    double sum = 0.0;
+    const size_t pairs = h->ev_used / 2;
+    for (size_t i = 0; i < pairs; i++) {
+        PD_TRY_HIP(hipEventSynchronize(h->ev_pool[2 * i + 1]), "event synchronize");
+        float ms = 0.f;
+        PD_TRY_HIP(hipEventElapsedTime(&ms, h->ev_pool[2 * i], h->ev_pool[2 * i + 1]), "event elapsed");
+        sum += ms;
+    }
+    *total_ms = sum;
+    *launches = (int32_t)pairs;
+    h->ev_used = 0;
+    return PD_OK;
+}
+
+pd_status pd_pack_matrix(const int8_t* w, int32_t K, int32_t N, void* packed_w, void* stream) {
+    if (!w || !packed_w) return fail(PD_ERR_NULL, "NULL device pointer");
+    if (K < 128 || K % 128 || N < 32 || N % 32) return fail(PD_ERR_SHAPE, "K must be a multiple of 128 and N a multiple of 32");
+    if (!aligned(packed_w, 256)) return fail(PD_ERR_ALIGN, "packed_w must be 256-byte aligned");
+    PD_TRY_HIP(pd::launch_pack_matrix(w, packed_w, K, N, 0, 0, 0, static_cast<hipStream_t>(stream)), "pack_matrix");
+    return PD_OK;
+}
+
+pd_status pd_pack_layer(pd_handle* h, const int8_t* w_in, const uint16_t* s_in, const int8_t* w_out,
+                        const uint16_t* s_out, const uint16_t* gamma, void* packed_layer, void* stream) {
+    if (!h) return fail(PD_ERR_NULL, "handle is NULL");
+    if (!w_in || !s_in || !w_out || !s_out || !gamma || !packed_layer) return fail(PD_ERR_NULL, "NULL device pointer");
+    if (!aligned(packed_layer, 256)) return fail(PD_ERR_ALIGN, "packed_layer must be 256-byte aligned");
+    const Shape& s = h->s;
+    const PackedLayout pl = packed_layout(s);
+    unsigned char* dst = static_cast<unsigned char*>(packed_layer);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    PD_TRY_HIP(pd::launch_pack_matrix(w_in, dst + pl.w_in, s.d, s.n_in, 1, s.n_qkv, s.F, st), "pack w_in");
+    PD_TRY_HIP(pd::launch_pack_matrix(w_out, dst + pl.w_out, s.k_out, s.d, 0, 0, 0, st), "pack w_out");
+    PD_TRY_HIP(pd::launch_pack_vector(s_in, reinterpret_cast<float*>(dst + pl.s_in), s.n_in, 1, s.n_qkv, s.F, st), "pack s_in");
+    PD_TRY_HIP(pd::launch_pack_vector(s_out, reinterpret_cast<float*>(dst + pl.s_out), s.d, 0, 0, 0, st), "pack s_out");
+    PD_TRY_HIP(pd::launch_pack_vector(gamma, reinterpret_cast<float*>(dst + pl.gamma), s.d, 0, 0, 0, st), "pack gamma");
+    return PD_OK;
+}
+
+static pd_status kv_convert(pd_handle* h, const void* src, void* dst, int32_t layer, int32_t B,
+                            int32_t L_ctx, int32_t is_v, int to_library, void* stream) {
+    if (!h) return fail(PD_ERR_NULL, "handle is NULL");
+    if (!src || !dst) return fail(PD_ERR_NULL, "NULL device pointer");
+    pd_status rc = check_batch(B, L_ctx);
+    if (rc != PD_OK) return rc;
+    if (layer < 0 || layer >= h->s.L) return fail(PD_ERR_RANGE, "layer out of range");
+    if (!aligned(src, 16) || !aligned(dst, 16)) return fail(PD_ERR_ALIGN, "cache pointers must be 16-byte aligned");
+    const size_t off = (size_t)layer * kv_layer_elems(h->s, B, L_ctx) * 2;
+    const void* s2 = to_library ? src : static_cast<const unsigned char*>(src) + off;
+    void* d2 = to_library ? static_cast<unsigned char*>(dst) + off : dst;
+    PD_TRY_HIP(pd::launch_kv_convert(s2, d2, B, L_ctx, h->s.dh, is_v ? 1 : 0, to_library,
+                                     static_cast<hipStream_t>(stream)), "kv_convert");
+    return PD_OK;
+}
+
+pd_status pd_kv_import(pd_handle* h, const uint16_t* canonical, void* cache, int32_t layer, int32_t B,
+                       int32_t L_ctx, int32_t is_v, void* stream) {
+    return kv_convert(h, canonical, cache, layer, B, L_ctx, is_v, 1, stream);
+}
+
+pd_status pd_kv_export(pd_handle* h, const void* cache, uint16_t* canonical, int32_t layer, int32_t B,
+                       int32_t L_ctx, int32_t is_v, void* stream) {
+    return kv_convert(h, cache, canonical, layer, B, L_ctx, is_v, 0, stream);
+}
+
+pd_status pd_decode_step(pd_handle* h, const void* packed_weights, void* k_cache, void* v_cache,
+                         const uint16_t* x_in, const int32_t* positions, int32_t B, int32_t L_ctx,
+                         uint16_t* x_out, void* workspace, size_t workspace_bytes, void* stream) {
+    pd_status rc = check_step_args(h, packed_weights, k_cache, v_cache, x_in, positions, B, L_ctx, x_out,
+                                   workspace, workspace_bytes);
+    if (rc != PD_OK) return rc;
+    StepArgs a{static_cast<const unsigned char*>(packed_weights), k_cache, v_cache, x_in, positions, B, L_ctx,
+               x_out, nullptr, 1, 0, h->s.L, static_cast<unsigned char*>(workspace)};
+    return run_layers(h, a, static_cast<hipStream_t>(stream));
+}
+
+pd_status pd_decode_layer(pd_handle* h, int32_t layer, const void* packed_layer, void* k_cache,
+                          void* v_cache, const uint16_t* x_in, const int32_t* positions, int32_t B,
+                          int32_t L_ctx, float* y_out, int32_t add_residual, void* workspace,
+                          size_t workspace_bytes, void* stream) {
+    pd_status rc = check_step_args(h, packed_layer, k_cache, v_cache, x_in, positions, B, L_ctx, y_out,
+                                   workspace, workspace_bytes);
+    if (rc != PD_OK) return rc;
+    if (layer < 0 || layer >= h->s.L) return fail(PD_ERR_RANGE, "layer out of range");
+    StepArgs a{static_cast<const unsigned char*>(packed_layer), k_cache, v_cache, x_in, positions, B, L_ctx,
+               nullptr, y_out, add_residual ? 1 : 0, layer, 1, static_cast<unsigned char*>(workspace)};
+    return run_layers(h, a, static_cast<hipStream_t>(stream));
+}
+
+pd_status pd_check_async(pd_handle* h, void* workspace, void* stream) {
+    if (!h || !workspace) return fail(PD_ERR_NULL, "NULL argument");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    PD_TRY_HIP(hipStreamSynchronize(st), "stream synchronize");
+    int32_t flags[256];
+    PD_TRY_HIP(hipMemcpy(flags, workspace, sizeof(flags), hipMemcpyDeviceToHost), "read flags");
+    for (int b = 0; b < 256; b++)
+        if (flags[b]) {
+            snprintf(g_err, sizeof(g_err), "positions[%d] was outside [0, L_ctx); that row was skipped", b);
+            return PD_ERR_POSITION;
+        }
+    return PD_OK;
+}
+
+pd_status pd_qgemm_workspace_bytes(int32_t B, int32_t K, int32_t N, size_t* bytes) {
+    if (!bytes) return fail(PD_ERR_NULL, "bytes is NULL");
+    if (B < 1 || B > 256 || K < 128 || K % 128 || N < 32 || N % 32) return fail(PD_ERR_SHAPE, "unsupported GEMM shape");
+    *bytes = align256((size_t)PD_MAX_SPLITS * B * N * 4);
+    return PD_OK;
+}
+
+pd_status pd_qgemm(const void* packed_w, const float* scale, const uint16_t* a, int32_t B, int32_t K,
+                   int32_t N, float* out, int32_t k_splits, void* workspace, size_t workspace_bytes,
+                   void* stream) {
+    if (!packed_w || !scale || !a || !out || !workspace) return fail(PD_ERR_NULL, "NULL device pointer");
+    size_t need = 0;
+    pd_status rc = pd_qgemm_workspace_bytes(B, K, N, &need);
+    if (rc != PD_OK) return rc;
+    if (workspace_bytes < need) return fail(PD_ERR_WORKSPACE, "workspace too small");
+    if (!aligned(packed_w, 256) || !aligned(workspace, 256) || !aligned(a, 16) || !aligned(out, 16))
+        return fail(PD_ERR_ALIGN, "misaligned device pointer");
+    if (k_splits < 0 || k_splits > PD_MAX_SPLITS || k_splits > K / 128) return fail(PD_ERR_RANGE, "k_splits out of range");
+    const int S = k_splits > 0 ? k_splits : pd::qgemm_auto_splits(B, K, N);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    float* part = static_cast<float*>(workspace);
+    PD_TRY_HIP(pd::launch_qgemm(packed_w, a, part, B, K, N, K, S, st), "qgemm");
+    PD_TRY_HIP(pd::launch_qgemm_reduce(part, scale, out, B, N, S, st), "qgemm_reduce");
+    return PD_OK;
+}
+
+pd_status pd_mqa_attend(pd_handle* h, int32_t layer, const uint16_t* q, const void* k_cache,
+                        const void* v_cache, const int32_t* positions, int32_t B, int32_t L_ctx,
+                        uint16_t* o, void* workspace, size_t workspace_bytes, void* stream) {
+    if (!h) return fail(PD_ERR_NULL, "handle is NULL");
+    if (!q || !k_cache || !v_cache || !positions || !o || !workspace) return fail(PD_ERR_NULL, "NULL device pointer");
+    pd_status rc = check_batch(B, L_ctx);
+    if (rc != PD_OK) return rc;
+    if (layer < 0 || layer >= h->s.L) return fail(PD_ERR_RANGE, "layer out of range");
+    if (!aligned(k_cache, 256) || !aligned(v_cache, 256) || !aligned(workspace, 256) || !aligned(q, 16) || !aligned(o, 16))
+        return fail(PD_ERR_ALIGN, "misaligned device pointer");
+    const Shape& s = h->s;
+    const Workspace w = workspace_layout(s, B, L_ctx);
+    if (workspace_bytes < w.total) return fail(PD_ERR_WORKSPACE, "workspace too small");
+    unsigned char* ws = static_cast<unsigned char*>(workspace);
+    const int bps = h->opt_bps > 0 ? h->opt_bps : auto_bps(B, L_ctx);
+    const size_t off = (size_t)layer * kv_layer_elems(s, B, L_ctx) * 2;
+    PD_TRY_HIP(pd::launch_mqa_attend(q, static_cast<const unsigned char*>(k_cache) + off,
+                                     static_cast<const unsigned char*>(v_cache) + off, positions, B, s.H,
+                                     s.dh, L_ctx, bps, reinterpret_cast<float*>(ws + w.opart),
+                                     reinterpret_cast<float*>(ws + w.ml), o, s.H * s.dh,
+                                     static_cast<hipStream_t>(stream)), "mqa_attend");
+    return PD_OK;
+}
+
+pd_status pd_graph_capture(pd_handle* h, const void* packed_weights, void* k_cache, void* v_cache,
+                           const uint16_t* x_in, const int32_t* positions, int32_t B, int32_t L_ctx,
+                           uint16_t* x_out, void* workspace, size_t workspace_bytes, void* stream) {
+    pd_status rc = check_step_args(h, packed_weights, k_cache, v_cache, x_in, positions, B, L_ctx, x_out,
+                                   workspace, workspace_bytes);
+    if (rc != PD_OK) return rc;
+    if (!stream) return fail(PD_ERR_STATE, "graph capture needs a non-null stream");
+    if (h->profile_kernel) return fail(PD_ERR_STATE, "turn profile_kernel off before capturing");
+    pd_graph_release(h);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    PD_TRY_HIP(hipStreamBeginCapture(st, hipStreamCaptureModeThreadLocal), "begin capture");
+    StepArgs a{static_cast<const unsigned char*>(packed_weights), k_cache, v_cache, x_in, positions, B, L_ctx,
+               x_out, nullptr, 1, 0, h->s.L, static_cast<unsigned char*>(workspace)};
+    rc = run_layers(h, a, st);
+    hipGraph_t g = nullptr;
+    hipError_t e = hipStreamEndCapture(st, &g);
+    if (rc != PD_OK) { if (g) (void)hipGraphDestroy(g); return rc; }
+    if (e != hipSuccess) return fail_hip(e, "end capture");
+    h->graph = g;
+    e = hipGraphInstantiate(&h->graph_exec, g, nullptr, nullptr, 0);
+    if (e != hipSuccess) { pd_graph_release(h); return fail_hip(e, "graph instantiate"); }
+    return PD_OK;
+}
+
+pd_status pd_graph_replay(pd_handle* h, void* stream) {
+    if (!h) return fail(PD_ERR_NULL, "handle is NULL");
+    if (!h->graph_exec) return fail(PD_ERR_STATE, "no captured graph");
+    PD_TRY_HIP(hipGraphLaunch(h->graph_exec, static_cast<hipStream_t>(stream)), "graph launch");
+    return PD_OK;
+}
+
+}  // extern "C"

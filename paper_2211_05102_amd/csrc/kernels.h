@@ -1,0 +1,44 @@
+// Host-side launchers of the gfx950 kernels (internal to the library).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#define PD_MAX_SPLITS 16          // K-splits of a projection
+#define PD_MIN_BLOCKS_PER_SPLIT 4 // 32-token blocks per attention workgroup, lower bound
+
+namespace pd {
+
+// ---- qgemm.hip
+void qgemm_config(int B, int* bm, int* ns, int* tile_cols);
+int qgemm_auto_splits(int B, int K, int N);
+hipError_t launch_qgemm(const void* wp, const uint16_t* a, float* part, int B, int K, int N,
+                        int lda, int S, hipStream_t stream);
+hipError_t launch_pack_matrix(const int8_t* w, void* dst, int K, int N, int mode, int n_qkv, int F,
+                              hipStream_t stream);
+hipError_t launch_pack_vector(const uint16_t* src, float* dst, int N, int mode, int n_qkv, int F,
+                              hipStream_t stream);
+hipError_t launch_qgemm_reduce(const float* part, const float* scale, float* out, int B, int N,
+                               int S, hipStream_t stream);
+
+// ---- attention.hip
+hipError_t launch_mqa_attend(const uint16_t* q, const void* kc_layer, const void* vc_layer,
+                             const int32_t* positions, int B, int H, int dh, int L_ctx, int bps,
+                             float* opart, float* ml, uint16_t* o, int o_stride,
+                             hipStream_t stream);
+hipError_t launch_kv_convert(const void* src, void* dst, int B, int L_ctx, int dh, int is_v,
+                             int to_library, hipStream_t stream);
+
+// ---- pointwise.hip
+hipError_t launch_prep(const int32_t* positions, int B, int L_ctx, int dh, float rope_base,
+                       float* cs, int32_t* flag, hipStream_t stream);
+hipError_t launch_ln_first(const uint16_t* x_in, const float* gamma, int B, int d, float eps,
+                           float* xres, uint16_t* h, hipStream_t stream);
+hipError_t launch_epi_in(const float* part, int S, const float* scale, const float* cs,
+                         const int32_t* positions, int B, int H, int dh, int F, int L_ctx,
+                         uint16_t* q, void* kc_layer, void* vc_layer, uint16_t* act, int act_stride,
+                         hipStream_t stream);
+hipError_t launch_epi_out(const float* part, int S, const float* scale, float* xres,
+                          const float* gamma_next, int B, int d, float eps, int add_residual,
+                          uint16_t* h, uint16_t* x_out_bf16, float* y_out_f32, hipStream_t stream);
+
+}  // namespace pd
