@@ -179,18 +179,20 @@ pd_status pd_check_async(pd_handle* h, void* workspace, void* stream);
 
 /* out[b][n] = s[n] * sum_k a[b][k] * w[k][n]   (Section 3.6 weight-only int8)
  *   packed_w from pd_pack_matrix, scale [N] fp32 device, a [B][K] bf16 device,
- *   out [B][N] fp32 device, B <= 256.  workspace >= pd_qgemm_workspace_bytes(). */
+ *   out [B][N] fp32 device, B <= 256.  workspace >= pd_qgemm_workspace_bytes().
+ *   The activations are converted to the library's 3-digit block fixed point
+ *   (23 bits relative to each 128-element chunk's maximum) before the product. */
 pd_status pd_qgemm_workspace_bytes(int32_t B, int32_t K, int32_t N, size_t* bytes);
 pd_status pd_qgemm(const void* packed_w, const float* scale, const uint16_t* a, int32_t B,
                    int32_t K, int32_t N, float* out, int32_t k_splits, void* workspace,
                    size_t workspace_bytes, void* stream);
 
 /* Multiquery attention of one layer over the library-layout cache (Section 3.3):
- *   q [B][H][dh] bf16 (already rotated), o [B][H*dh] bf16,
+ *   q [B][H][dh] fp32 (already rotated, unscaled), o [B][H*dh] fp32,
  *   attends over slots 0..positions[b] of layer `layer`. */
-pd_status pd_mqa_attend(pd_handle* h, int32_t layer, const uint16_t* q, const void* k_cache,
+pd_status pd_mqa_attend(pd_handle* h, int32_t layer, const float* q, const void* k_cache,
                         const void* v_cache, const int32_t* positions, int32_t B, int32_t L_ctx,
-                        uint16_t* o, void* workspace, size_t workspace_bytes, void* stream);
+                        float* o, void* workspace, size_t workspace_bytes, void* stream);
 
 /* ---- graph replay --------------------------------------------------------- */
 

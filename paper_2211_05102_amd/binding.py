@@ -193,6 +193,7 @@ class Decoder:
 
     def mqa_attend(self, layer, q, k_cache, v_cache, positions, L_ctx, o, workspace, stream=None) -> None:
         B = q.shape[0]
+        assert q.dtype == torch.float32 and o.dtype == torch.float32 and q.is_contiguous()
         _check(lib().pd_mqa_attend(self._h, ctypes.c_int32(layer), _ptr(q), _ptr(k_cache), _ptr(v_cache),
                                    _ptr(positions), ctypes.c_int32(B), ctypes.c_int32(L_ctx), _ptr(o),
                                    _ptr(workspace),

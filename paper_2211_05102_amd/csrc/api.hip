@@ -37,9 +37,9 @@ pd_status check_desc(const pd_model_desc* m, Shape* s) {
     if (m->d_head != 64 && m->d_head != 128 && m->d_head != 256) return fail(PD_ERR_SHAPE, "d_head must be 64, 128 or 256");
     if (m->n_heads < 1 || m->n_heads > 32) return fail(PD_ERR_SHAPE, "n_heads must be in 1..32");
     if (m->n_kv_heads != 1) return fail(PD_ERR_SHAPE, "n_kv_heads must be 1 (multiquery)");
-    if (m->d_ff < 32 || m->d_ff % 32) return fail(PD_ERR_SHAPE, "d_ff must be a positive multiple of 32");
+    if (m->d_ff < 128 || m->d_ff % 128) return fail(PD_ERR_SHAPE, "d_ff must be a positive multiple of 128");
     long long k_out = (long long)m->n_heads * m->d_head + m->d_ff;
-    if (k_out % 128) return fail(PD_ERR_SHAPE, "n_heads*d_head + d_ff must be a multiple of 128");
+    if ((m->n_heads * m->d_head) % 128) return fail(PD_ERR_SHAPE, "n_heads*d_head must be a multiple of 128");
     long long n_in = (long long)m->n_heads * m->d_head + 2LL * m->d_head + 2LL * m->d_ff;
     if (n_in > (1 << 24) || k_out > (1 << 24) || m->d_model > (1 << 20)) return fail(PD_ERR_SHAPE, "model too large");
     if (!(m->rope_base > 1.0f) || !(m->ln_eps > 0.0f)) return fail(PD_ERR_SHAPE, "rope_base must exceed 1 and ln_eps must be positive");
@@ -82,7 +82,7 @@ int auto_bps(int B, int L_ctx) {
 
 // workspace carving; sized for the largest split counts so options never overflow it
 struct Workspace {
-    size_t flag, cs, xres, h, part_in, q, act, opart, ml, part_out, total;
+    size_t flag, cs, xres, h, hs, part_in, q, act, acts, opart, ml, part_out, total;
 };
 Workspace workspace_layout(const Shape& s, int B, int L_ctx) {
     Workspace w;
@@ -91,10 +91,12 @@ Workspace workspace_layout(const Shape& s, int B, int L_ctx) {
     w.flag = o; o += 1024;  // 256 per-row position flags
     w.cs = o; o += align256((size_t)B * (s.dh / 2) * 2 * 4);
     w.xres = o; o += align256((size_t)B * s.d * 4);
-    w.h = o; o += align256((size_t)B * s.d * 2);
+    w.h = o; o += align256((size_t)B * s.d * 3);                    // digit planes of LN(x)
+    w.hs = o; o += align256((size_t)(s.d / 128) * 256 * 4);         // their scales [chunk][256]
     w.part_in = o; o += align256((size_t)PD_MAX_SPLITS * B * s.n_in * 4);
-    w.q = o; o += align256((size_t)B * s.H * s.dh * 2);
-    w.act = o; o += align256((size_t)B * s.k_out * 2);
+    w.q = o; o += align256((size_t)B * s.H * s.dh * 4);
+    w.act = o; o += align256((size_t)B * s.k_out * 3);              // digit planes of [o | a]
+    w.acts = o; o += align256((size_t)(s.k_out / 128) * 256 * 4);
     w.opart = o; o += align256((size_t)B * nsplit_max * s.H * s.dh * 4);
     w.ml = o; o += align256((size_t)B * nsplit_max * s.H * 2 * 4);
     w.part_out = o; o += align256((size_t)PD_MAX_SPLITS * B * s.d * 4);
@@ -110,6 +112,7 @@ struct pd_handle {
     pd_model_desc desc;
     Shape s;
     int opt_split_in = 0, opt_split_out = 0, opt_bps = 0;
+    int act_digits = 3;  // int8 digit planes per projection operand
     hipGraph_t graph = nullptr;
     hipGraphExec_t graph_exec = nullptr;
     // optional event timing of one kernel class (0 = off), see pd_profile_read
@@ -162,10 +165,12 @@ pd_status run_layers(pd_handle* h, const StepArgs& a, hipStream_t st) {
     float* cs = reinterpret_cast<float*>(a.ws + w.cs);
     int32_t* flag = reinterpret_cast<int32_t*>(a.ws + w.flag);
     float* xres = reinterpret_cast<float*>(a.ws + w.xres);
-    uint16_t* hbuf = reinterpret_cast<uint16_t*>(a.ws + w.h);
+    unsigned char* hq = a.ws + w.h;
+    float* hs = reinterpret_cast<float*>(a.ws + w.hs);
     float* part_in = reinterpret_cast<float*>(a.ws + w.part_in);
-    uint16_t* q = reinterpret_cast<uint16_t*>(a.ws + w.q);
-    uint16_t* act = reinterpret_cast<uint16_t*>(a.ws + w.act);
+    float* q = reinterpret_cast<float*>(a.ws + w.q);
+    unsigned char* actq = a.ws + w.act;
+    float* acts = reinterpret_cast<float*>(a.ws + w.acts);
     float* opart = reinterpret_cast<float*>(a.ws + w.opart);
     float* ml = reinterpret_cast<float*>(a.ws + w.ml);
     float* part_out = reinterpret_cast<float*>(a.ws + w.part_out);
@@ -173,6 +178,7 @@ pd_status run_layers(pd_handle* h, const StepArgs& a, hipStream_t st) {
     const int S_in = h->opt_split_in > 0 ? h->opt_split_in : pd::qgemm_auto_splits(B, s.d, s.n_in);
     const int S_out = h->opt_split_out > 0 ? h->opt_split_out : pd::qgemm_auto_splits(B, s.k_out, s.d);
     const int bps = h->opt_bps > 0 ? h->opt_bps : auto_bps(B, a.L_ctx);
+    const int nd = h->act_digits;
     const size_t kv_layer_bytes = kv_layer_elems(s, B, a.L_ctx) * 2;
 
     PD_TRY_HIP(pd::launch_prep(a.positions, B, a.L_ctx, s.dh, h->desc.rope_base, cs, flag, st), "prep");
@@ -184,27 +190,30 @@ pd_status run_layers(pd_handle* h, const StepArgs& a, hipStream_t st) {
         unsigned char* kc = static_cast<unsigned char*>(a.k_cache) + (size_t)(a.layer0 + i) * kv_layer_bytes;
         unsigned char* vc = static_cast<unsigned char*>(a.v_cache) + (size_t)(a.layer0 + i) * kv_layer_bytes;
         if (i == 0)
-            PD_TRY_HIP(pd::launch_ln_first(a.x_in, gamma, B, s.d, h->desc.ln_eps, xres, hbuf, st), "ln_first");
+            PD_TRY_HIP(pd::launch_ln_first(a.x_in, gamma, B, s.d, h->desc.ln_eps, xres, hq, hs, nd, st), "ln_first");
         prof_mark(h, PROF_QGEMM_IN, st);
-        PD_TRY_HIP(pd::launch_qgemm(L + pl.w_in, hbuf, part_in, B, s.d, s.n_in, s.d, S_in, st), "qgemm_in");
+        PD_TRY_HIP(pd::launch_qgemm(L + pl.w_in, hq, hs, part_in, B, s.d, s.n_in, S_in, nd, st), "qgemm_in");
         prof_mark(h, PROF_QGEMM_IN, st);
         prof_mark(h, PROF_EPI_IN, st);
         PD_TRY_HIP(pd::launch_epi_in(part_in, S_in, s_in, cs, a.positions, B, s.H, s.dh, s.F, a.L_ctx, q,
-                                     kc, vc, act, s.k_out, st), "epi_in");
+                                     kc, vc, actq, acts, nd, st), "epi_in");
         prof_mark(h, PROF_EPI_IN, st);
         prof_mark(h, PROF_ATTEND, st);
         PD_TRY_HIP(pd::launch_mqa_attend(q, kc, vc, a.positions, B, s.H, s.dh, a.L_ctx, bps, opart, ml,
-                                         act, s.k_out, st), "mqa_attend");
+                                         nullptr, actq, acts, s.k_out, nd, st), "mqa_attend");
         prof_mark(h, PROF_ATTEND, st);
         prof_mark(h, PROF_QGEMM_OUT, st);
-        PD_TRY_HIP(pd::launch_qgemm(L + pl.w_out, act, part_out, B, s.k_out, s.d, s.k_out, S_out, st), "qgemm_out");
+        PD_TRY_HIP(pd::launch_qgemm(L + pl.w_out, actq, acts, part_out, B, s.k_out, s.d, S_out, nd, st), "qgemm_out");
         prof_mark(h, PROF_QGEMM_OUT, st);
         const bool last = i == a.n_run - 1;
-        const float* gamma_next = last ? nullptr : reinterpret_cast<const float*>(L + pl.total + pl.gamma);
         prof_mark(h, PROF_EPI_OUT, st);
-        PD_TRY_HIP(pd::launch_epi_out(part_out, S_out, s_out, xres, gamma_next, B, s.d, h->desc.ln_eps,
-                                      a.add_residual, hbuf, last ? a.x_out_bf16 : nullptr,
-                                      last ? a.y_out_f32 : nullptr, st), "epi_out");
+        PD_TRY_HIP(pd::launch_residual(part_out, S_out, s_out, xres, B, s.d, a.add_residual,
+                                       last ? a.x_out_bf16 : nullptr, last ? a.y_out_f32 : nullptr, st),
+                   "residual");
+        if (!last) {
+            const float* gamma_next = reinterpret_cast<const float*>(L + pl.total + pl.gamma);
+            PD_TRY_HIP(pd::launch_ln(xres, gamma_next, B, s.d, h->desc.ln_eps, hq, hs, nd, st), "ln");
+        }
         prof_mark(h, PROF_EPI_OUT, st);
     }
     return PD_OK;
@@ -316,6 +325,11 @@ pd_status pd_set_option(pd_handle* h, const char* name, int32_t value) {
     if (!strcmp(name, "attn_blocks_per_split")) {
         if (value != 0 && (value < PD_MIN_BLOCKS_PER_SPLIT || value > 4096)) return fail(PD_ERR_RANGE, "attn_blocks_per_split must be 0 or in 4..4096");
         h->opt_bps = value;
+        return PD_OK;
+    }
+    if (!strcmp(name, "act_digits")) {
+        if (value != 2 && value != 3) return fail(PD_ERR_RANGE, "act_digits must be 2 or 3");
+        h->act_digits = value;
         return PD_OK;
     }
     if (!strcmp(name, "profile_kernel")) {
@@ -435,7 +449,8 @@ pd_status pd_check_async(pd_handle* h, void* workspace, void* stream) {
 pd_status pd_qgemm_workspace_bytes(int32_t B, int32_t K, int32_t N, size_t* bytes) {
     if (!bytes) return fail(PD_ERR_NULL, "bytes is NULL");
     if (B < 1 || B > 256 || K < 128 || K % 128 || N < 32 || N % 32) return fail(PD_ERR_SHAPE, "unsupported GEMM shape");
-    *bytes = align256((size_t)PD_MAX_SPLITS * B * N * 4);
+    *bytes = align256((size_t)PD_MAX_SPLITS * B * N * 4) + align256((size_t)B * K * 3) +
+             align256((size_t)(K / 128) * 256 * 4);
     return PD_OK;
 }
 
@@ -452,15 +467,19 @@ pd_status pd_qgemm(const void* packed_w, const float* scale, const uint16_t* a, 
     if (k_splits < 0 || k_splits > PD_MAX_SPLITS || k_splits > K / 128) return fail(PD_ERR_RANGE, "k_splits out of range");
     const int S = k_splits > 0 ? k_splits : pd::qgemm_auto_splits(B, K, N);
     hipStream_t st = static_cast<hipStream_t>(stream);
-    float* part = static_cast<float*>(workspace);
-    PD_TRY_HIP(pd::launch_qgemm(packed_w, a, part, B, K, N, K, S, st), "qgemm");
+    unsigned char* wsb = static_cast<unsigned char*>(workspace);
+    float* part = reinterpret_cast<float*>(wsb);
+    unsigned char* qa = wsb + align256((size_t)PD_MAX_SPLITS * B * N * 4);
+    float* qs = reinterpret_cast<float*>(qa + align256((size_t)B * K * 3));
+    PD_TRY_HIP(pd::launch_quantize_bf16(a, qa, qs, B, K, 3, st), "quantize");
+    PD_TRY_HIP(pd::launch_qgemm(packed_w, qa, qs, part, B, K, N, S, 3, st), "qgemm");
     PD_TRY_HIP(pd::launch_qgemm_reduce(part, scale, out, B, N, S, st), "qgemm_reduce");
     return PD_OK;
 }
 
-pd_status pd_mqa_attend(pd_handle* h, int32_t layer, const uint16_t* q, const void* k_cache,
+pd_status pd_mqa_attend(pd_handle* h, int32_t layer, const float* q, const void* k_cache,
                         const void* v_cache, const int32_t* positions, int32_t B, int32_t L_ctx,
-                        uint16_t* o, void* workspace, size_t workspace_bytes, void* stream) {
+                        float* o, void* workspace, size_t workspace_bytes, void* stream) {
     if (!h) return fail(PD_ERR_NULL, "handle is NULL");
     if (!q || !k_cache || !v_cache || !positions || !o || !workspace) return fail(PD_ERR_NULL, "NULL device pointer");
     pd_status rc = check_batch(B, L_ctx);
@@ -477,8 +496,8 @@ pd_status pd_mqa_attend(pd_handle* h, int32_t layer, const uint16_t* q, const vo
     PD_TRY_HIP(pd::launch_mqa_attend(q, static_cast<const unsigned char*>(k_cache) + off,
                                      static_cast<const unsigned char*>(v_cache) + off, positions, B, s.H,
                                      s.dh, L_ctx, bps, reinterpret_cast<float*>(ws + w.opart),
-                                     reinterpret_cast<float*>(ws + w.ml), o, s.H * s.dh,
-                                     static_cast<hipStream_t>(stream)), "mqa_attend");
+                                     reinterpret_cast<float*>(ws + w.ml), o, nullptr, nullptr, s.k_out,
+                                     h->act_digits, static_cast<hipStream_t>(stream)), "mqa_attend");
     return PD_OK;
 }
 

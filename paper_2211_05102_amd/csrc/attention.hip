@@ -18,6 +18,12 @@
 //   K block (32 tokens): uint4 index (j*64 + lane)       = K[t = lane%32][16j + 8(lane/32) + 0..7]
 //   V block: uint4 index ((db*2 + kk)*64 + lane), element e
 //            = V[t = 16kk + 8(e/4) + 4(lane/32) + e%4][c = 32db + lane%32]
+// K and V are bf16 data and enter the MFMAs exactly.  The two operands this
+// kernel creates itself, q (pre-multiplied by log2(e)/sqrt(dh)) and the softmax
+// weights P, are each split into a bf16 head and a bf16 remainder (hi + lo, 16
+// significant bits) and cost two MFMAs per step: the matrix pipe has an order of
+// magnitude of slack in this HBM-bound kernel, and a single bf16 rounding of q
+// and P would be the largest error of the whole step.
 // Split-KV: workgroup (split, b) takes `bps` consecutive 32-token blocks, its 4
 // waves take them round-robin with a running (max, sum, acc) each (base-2
 // exponentials, Section 3.5), merge through LDS, and write one fp32 partial; a
@@ -29,14 +35,17 @@ namespace pd {
 
 template <int DH>
 __global__ __launch_bounds__(256) void mqa_attend_kernel(
-    const uint16_t* __restrict__ q, const uint4* __restrict__ kc, const uint4* __restrict__ vc,
+    const float* __restrict__ q, const uint4* __restrict__ kc, const uint4* __restrict__ vc,
     const int32_t* __restrict__ positions, int H, int L_ctx, int bps, int nsplit,
     float* __restrict__ opart, float* __restrict__ ml, float scale_log2e) {
     constexpr int KJ = DH / 16;  // MFMA steps of the q.K product
     constexpr int DB = DH / 32;  // 32-channel blocks of the output
     constexpr int BLK_U4 = 4 * DH;  // uint4 per 32-token block (K and V alike)
     __shared__ float ml_s[4][64][2];
-    __shared__ float obuf[DB * 16][64];
+    // q operands [plane][j][lane] during the block loop, then the merge buffer [DB*16][64] floats
+    __shared__ uint4 smem[2 * KJ * 64];
+    static_assert(sizeof(uint4) * 2 * KJ * 64 >= sizeof(float) * DB * 16 * 64, "merge buffer fits");
+    float (*obuf)[64] = reinterpret_cast<float (*)[64]>(smem);
 
     const int b = blockIdx.y, split = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -49,12 +58,24 @@ __global__ __launch_bounds__(256) void mqa_attend_kernel(
     if (blk0 >= blk1) return;
     const int nblk_cap = L_ctx >> 5;
 
-    // q operand (B matrix): lane (head l32, g) holds q[h][16j + 8g .. +8) for every j
-    const int hq = l32 < H ? l32 : H - 1;  // padded heads duplicate the last one; never stored
-    uint4 qop[KJ];
-#pragma unroll
-    for (int j = 0; j < KJ; j++)
-        qop[j] = *reinterpret_cast<const uint4*>(q + ((size_t)b * H + hq) * DH + 16 * j + 8 * g);
+    // q operand (B matrix): slot (j, lane = (head, g)) holds q[h][16j + 8g .. +8) * log2(e)/sqrt(dh),
+    // split into bf16 hi (plane 0) and lo (plane 1).  Padded heads duplicate the last one.
+    for (int slot = tid; slot < KJ * 64; slot += 256) {
+        const int j = slot >> 6, ln = slot & 63;
+        const int hh = (ln & 31) < H ? (ln & 31) : H - 1;
+        const float* src = q + ((size_t)b * H + hh) * DH + 16 * j + 8 * (ln >> 5);
+        const f32x4 a0 = *reinterpret_cast<const f32x4*>(src) * scale_log2e;
+        const f32x4 a1 = *reinterpret_cast<const f32x4*>(src + 4) * scale_log2e;
+        const uint4 hi = {pack_bf16x2(a0.x, a0.y), pack_bf16x2(a0.z, a0.w), pack_bf16x2(a1.x, a1.y),
+                          pack_bf16x2(a1.z, a1.w)};
+        const uint4 lo = {pack_bf16x2(a0.x - bf16_lo(hi.x), a0.y - bf16_hi(hi.x)),
+                          pack_bf16x2(a0.z - bf16_lo(hi.y), a0.w - bf16_hi(hi.y)),
+                          pack_bf16x2(a1.x - bf16_lo(hi.z), a1.y - bf16_hi(hi.z)),
+                          pack_bf16x2(a1.z - bf16_lo(hi.w), a1.w - bf16_hi(hi.w))};
+        smem[slot] = hi;
+        smem[KJ * 64 + slot] = lo;
+    }
+    __syncthreads();
 
     const uint4* kbase = kc + (size_t)b * nblk_cap * BLK_U4 + lane;
     const uint4* vbase = vc + (size_t)b * nblk_cap * BLK_U4 + lane;
@@ -81,12 +102,14 @@ __global__ __launch_bounds__(256) void mqa_attend_kernel(
 #pragma unroll
         for (int r = 0; r < 16; r++) S[r] = 0.f;
 #pragma unroll
-        for (int j = 0; j < KJ; j++)
-            S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kreg[j]),
-                                                        __builtin_bit_cast(bf16x8, qop[j]), S, 0, 0, 0);
+        for (int j = 0; j < KJ; j++) {
+            const bf16x8 kop = __builtin_bit_cast(bf16x8, kreg[j]);
+            S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                kop, __builtin_bit_cast(bf16x8, smem[j * 64 + lane]), S, 0, 0, 0);
+            S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                kop, __builtin_bit_cast(bf16x8, smem[(KJ + j) * 64 + lane]), S, 0, 0, 0);
+        }
         const bool tail = (blk == nblk - 1) && ((P & 31) != 31);
-#pragma unroll
-        for (int r = 0; r < 16; r++) S[r] *= scale_log2e;
         if (tail) {
 #pragma unroll
             for (int r = 0; r < 16; r++) {
@@ -127,20 +150,29 @@ __global__ __launch_bounds__(256) void mqa_attend_kernel(
 #pragma unroll
                 for (int r = 0; r < 16; r++) O[db][r] *= alpha;
         }
-        bf16x8 pop[2];
+        bf16x8 pop[2][2];  // [kk][hi, lo]
 #pragma unroll
         for (int kk = 0; kk < 2; kk++) {
-            uint4 pk = {pack_bf16x2(S[8 * kk + 0], S[8 * kk + 1]), pack_bf16x2(S[8 * kk + 2], S[8 * kk + 3]),
-                        pack_bf16x2(S[8 * kk + 4], S[8 * kk + 5]), pack_bf16x2(S[8 * kk + 6], S[8 * kk + 7])};
-            pop[kk] = __builtin_bit_cast(bf16x8, pk);
+            uint32_t hi[4], lo[4];
+#pragma unroll
+            for (int e = 0; e < 4; e++) {
+                const float p0 = S[8 * kk + 2 * e], p1 = S[8 * kk + 2 * e + 1];
+                hi[e] = pack_bf16x2(p0, p1);
+                lo[e] = pack_bf16x2(p0 - bf16_lo(hi[e]), p1 - bf16_hi(hi[e]));
+            }
+            pop[kk][0] = __builtin_bit_cast(bf16x8, make_uint4(hi[0], hi[1], hi[2], hi[3]));
+            pop[kk][1] = __builtin_bit_cast(bf16x8, make_uint4(lo[0], lo[1], lo[2], lo[3]));
         }
 #pragma unroll
         for (int db = 0; db < DB; db++)
 #pragma unroll
-            for (int kk = 0; kk < 2; kk++)
-                O[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vreg[db][kk]),
-                                                                pop[kk], O[db], 0, 0, 0);
+            for (int kk = 0; kk < 2; kk++) {
+                const bf16x8 vop = __builtin_bit_cast(bf16x8, vreg[db][kk]);
+                O[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop, pop[kk][0], O[db], 0, 0, 0);
+                O[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop, pop[kk][1], O[db], 0, 0, 0);
+            }
     }
+    __syncthreads();  // every wave is done with the q operands: smem becomes the merge buffer
 
     // ---- merge the 4 waves (a wave without blocks has m = -inf, l = 0, O = 0)
     float l_tot = l_run + __shfl_xor(l_run, 32, 64);
@@ -191,30 +223,44 @@ __global__ __launch_bounds__(256) void mqa_attend_kernel(
     }
 }
 
-// o[b][h*dh + c] = sum_s w_s O_s[c] / sum_s w_s l_s,  w_s = 2^(m_s - max m), splits in index order
-__global__ __launch_bounds__(256) void mqa_combine_kernel(const float* __restrict__ opart,
-                                                          const float* __restrict__ ml,
-                                                          const int32_t* __restrict__ positions,
-                                                          int H, int dh, int L_ctx, int bps, int nsplit,
-                                                          uint16_t* __restrict__ o, int o_stride) {
+// o[b][h*dh + c] = sum_s w_s O_s[c] / sum_s w_s l_s,  w_s = 2^(m_s - max m), splits in index order.
+// One wavefront per 128-element chunk of the row (two adjacent channels per lane);
+// the result goes out as fp32 (`o`) and/or in block fixed point as the first
+// H*dh/128 chunks of the output projection's operand (`actq`, `acts`).
+__global__ __launch_bounds__(256) void mqa_combine_kernel(
+    const float* __restrict__ opart, const float* __restrict__ ml,
+    const int32_t* __restrict__ positions, int H, int dh, int L_ctx, int bps, int nsplit,
+    float* __restrict__ o, unsigned char* __restrict__ actq, float* __restrict__ acts,
+    int k_out, int nd) {
     const int b = blockIdx.y;
     const int P = positions[b];
     if (P < 0 || P >= L_ctx) return;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int j = blockIdx.x * 4 + wave;
+    if (j >= (H * dh >> 7)) return;
     const int live = ((P >> 5) + bps) / bps;  // ceil(nblk / bps), nblk = P/32 + 1
-    const int idx = blockIdx.x * 256 + threadIdx.x;  // over H*dh
-    if (idx >= H * dh) return;
+    const int idx = j * QCHUNK + 2 * lane;     // idx and idx + 1 lie in the same head
     const int h = idx / dh, c = idx - h * dh;
     const size_t row0 = (size_t)b * nsplit * H + h;
     float m_all = -INFINITY;
     for (int s = 0; s < live; s++) m_all = fmaxf(m_all, ml[(row0 + (size_t)s * H) * 2]);
-    float num = 0.f, den = 0.f;
+    float n0 = 0.f, n1 = 0.f, den = 0.f;
     for (int s = 0; s < live; s++) {
-        size_t row = row0 + (size_t)s * H;
-        float w = __builtin_amdgcn_exp2f(ml[row * 2] - m_all);
+        const size_t row = row0 + (size_t)s * H;
+        const float w = __builtin_amdgcn_exp2f(ml[row * 2] - m_all);
         den += w * ml[row * 2 + 1];
-        num += w * opart[row * dh + c];
+        const f32x2 ov = *reinterpret_cast<const f32x2*>(opart + row * dh + c);
+        n0 += w * ov.x;
+        n1 += w * ov.y;
     }
-    o[(size_t)b * o_stride + idx] = to_bf16(num / den);
+    const float o0 = n0 / den, o1 = n1 / den;
+    if (o) {
+        const f32x2 ov = {o0, o1};
+        *reinterpret_cast<f32x2*>(o + (size_t)b * H * dh + idx) = ov;
+    }
+    if (actq)
+        quantize_chunk_wave(o0, o1, lane, nd, actq + ((size_t)b * k_out + (size_t)j * QCHUNK) * nd,
+                            acts + (size_t)j * QSCALE_ROWS + b);
 }
 
 // canonical [B][L_ctx][dh]  <->  library block layout, one element per thread
@@ -241,10 +287,10 @@ __global__ __launch_bounds__(256) void kv_convert_kernel(const uint16_t* __restr
     else dst[idx] = src[lib];
 }
 
-hipError_t launch_mqa_attend(const uint16_t* q, const void* kc_layer, const void* vc_layer,
+hipError_t launch_mqa_attend(const float* q, const void* kc_layer, const void* vc_layer,
                              const int32_t* positions, int B, int H, int dh, int L_ctx, int bps,
-                             float* opart, float* ml, uint16_t* o, int o_stride,
-                             hipStream_t stream) {
+                             float* opart, float* ml, float* o, void* actq, float* acts,
+                             int k_out, int nd, hipStream_t stream) {
     const int nblk_cap = L_ctx / 32;
     const int nsplit = (nblk_cap + bps - 1) / bps;
     const float scale_log2e = 1.4426950408889634f / sqrtf((float)dh);
@@ -264,8 +310,9 @@ hipError_t launch_mqa_attend(const uint16_t* q, const void* kc_layer, const void
         return hipErrorInvalidValue;
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    mqa_combine_kernel<<<dim3((H * dh + 255) / 256, B), block, 0, stream>>>(
-        opart, ml, positions, H, dh, L_ctx, bps, nsplit, o, o_stride);
+    mqa_combine_kernel<<<dim3((H * dh / 128 + 3) / 4, B), block, 0, stream>>>(
+        opart, ml, positions, H, dh, L_ctx, bps, nsplit, o, reinterpret_cast<unsigned char*>(actq),
+        acts, k_out, nd);
     return hipGetLastError();
 }
 

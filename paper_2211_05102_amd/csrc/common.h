@@ -10,6 +10,8 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef int i32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int WAVE = 64;
 
@@ -33,6 +35,63 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ uint4 ld_stream(const uint4* p) {
     u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
     return make_uint4(v.x, v.y, v.z, v.w);
+}
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+
+// ---- block fixed-point activations ------------------------------------------
+// The operands of the two projections are stored as ND (2 or 3) int8 digit
+// planes with one power-of-two scale per (row, 128-element chunk):
+//     value ~= scale * sum_p 256^(ND-1-p) * d_p,   d_0 in [-127,127], others in [-128,127]
+// i.e. 8*ND - 1 bits + sign relative to the chunk maximum (ND = 3: fp32-grade),
+// which the int8 MFMA multiplies with the int8 weights exactly (int32 sums).
+// Row layout (bytes): chunk j of a row at j*128*ND: plane p at +128*p (plane 0 is
+// the most significant digit); row pitch = ND*K.
+// Scales are stored transposed, scale_t[chunk][256 rows], so that the four rows
+// a lane needs are contiguous.
+constexpr int QCHUNK = 128;
+constexpr int QSCALE_ROWS = 256;
+
+// One wavefront quantises one chunk: lane holds elements 2*lane and 2*lane+1.
+__device__ __forceinline__ void quantize_chunk_wave(float v0, float v1, int lane, int nd,
+                                                    unsigned char* __restrict__ row_chunk,
+                                                    float* __restrict__ scale_slot) {
+    const float mx = wave_max(fmaxf(fabsf(v0), fabsf(v1)));
+    const int top_bits = 8 * (nd - 1);                  // weight of the top digit = 2^top_bits
+    const float nmax = (float)(127 << top_bits);        // 32512 or 8323072
+    float s = 1.0f;
+    if (mx >= 1e-30f && mx < 1e30f) {
+        // smallest power of two with mx / s <= nmax
+        const int fl = (int)((__float_as_uint(mx) >> 23) & 0xff) - 127;  // floor(log2 mx)
+        s = __uint_as_float((uint32_t)(fl - (top_bits + 6) + 127) << 23);  // nmax < 2^(top_bits+7)
+        if (mx > nmax * s) s *= 2.0f;
+    }
+    const float inv = 1.0f / s;  // exact
+    const int lim = 127 << top_bits;
+    int n0 = (int)rintf(v0 * inv), n1 = (int)rintf(v1 * inv);
+    n0 = n0 > lim ? lim : (n0 < -lim ? -lim : n0);  // only NaN/inf inputs get here
+    n1 = n1 > lim ? lim : (n1 < -lim ? -lim : n1);
+    // digits from the least significant up: floor division keeps every lower digit in [-128,127]
+    for (int p = nd - 1; p >= 0; p--) {
+        int d0, d1;
+        if (p > 0) {
+            const int h0 = (n0 + 128) >> 8, h1 = (n1 + 128) >> 8;
+            d0 = n0 - (h0 << 8);
+            d1 = n1 - (h1 << 8);
+            n0 = h0;
+            n1 = h1;
+        } else {
+            d0 = n0;
+            d1 = n1;
+        }
+        *(reinterpret_cast<uint16_t*>(row_chunk + p * QCHUNK) + lane) =
+            (uint16_t)((d0 & 0xff) | ((d1 & 0xff) << 8));
+    }
+    if (lane == 0) *scale_slot = s;
 }
 
 __device__ __forceinline__ float wave_sum(float v) {

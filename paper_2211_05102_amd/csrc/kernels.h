@@ -11,8 +11,10 @@ namespace pd {
 // ---- qgemm.hip
 void qgemm_config(int B, int* bm, int* ns, int* tile_cols);
 int qgemm_auto_splits(int B, int K, int N);
-hipError_t launch_qgemm(const void* wp, const uint16_t* a, float* part, int B, int K, int N,
-                        int lda, int S, hipStream_t stream);
+hipError_t launch_qgemm(const void* wp, const void* qa, const float* scale_t, float* part, int B,
+                        int K, int N, int S, int nd, hipStream_t stream);
+hipError_t launch_quantize_bf16(const uint16_t* a, void* qa, float* scale_t, int B, int K, int nd,
+                                hipStream_t stream);
 hipError_t launch_pack_matrix(const int8_t* w, void* dst, int K, int N, int mode, int n_qkv, int F,
                               hipStream_t stream);
 hipError_t launch_pack_vector(const uint16_t* src, float* dst, int N, int mode, int n_qkv, int F,
@@ -21,10 +23,10 @@ hipError_t launch_qgemm_reduce(const float* part, const float* scale, float* out
                                int S, hipStream_t stream);
 
 // ---- attention.hip
-hipError_t launch_mqa_attend(const uint16_t* q, const void* kc_layer, const void* vc_layer,
+hipError_t launch_mqa_attend(const float* q, const void* kc_layer, const void* vc_layer,
                              const int32_t* positions, int B, int H, int dh, int L_ctx, int bps,
-                             float* opart, float* ml, uint16_t* o, int o_stride,
-                             hipStream_t stream);
+                             float* opart, float* ml, float* o, void* actq, float* acts,
+                             int k_out, int nd, hipStream_t stream);
 hipError_t launch_kv_convert(const void* src, void* dst, int B, int L_ctx, int dh, int is_v,
                              int to_library, hipStream_t stream);
 
@@ -32,13 +34,15 @@ hipError_t launch_kv_convert(const void* src, void* dst, int B, int L_ctx, int d
 hipError_t launch_prep(const int32_t* positions, int B, int L_ctx, int dh, float rope_base,
                        float* cs, int32_t* flag, hipStream_t stream);
 hipError_t launch_ln_first(const uint16_t* x_in, const float* gamma, int B, int d, float eps,
-                           float* xres, uint16_t* h, hipStream_t stream);
+                           float* xres, void* hq, float* hs, int nd, hipStream_t stream);
+hipError_t launch_ln(const float* xres, const float* gamma, int B, int d, float eps, void* hq,
+                     float* hs, int nd, hipStream_t stream);
 hipError_t launch_epi_in(const float* part, int S, const float* scale, const float* cs,
                          const int32_t* positions, int B, int H, int dh, int F, int L_ctx,
-                         uint16_t* q, void* kc_layer, void* vc_layer, uint16_t* act, int act_stride,
-                         hipStream_t stream);
-hipError_t launch_epi_out(const float* part, int S, const float* scale, float* xres,
-                          const float* gamma_next, int B, int d, float eps, int add_residual,
-                          uint16_t* h, uint16_t* x_out_bf16, float* y_out_f32, hipStream_t stream);
+                         float* q, void* kc_layer, void* vc_layer, void* actq, float* acts,
+                         int nd, hipStream_t stream);
+hipError_t launch_residual(const float* part, int S, const float* scale, float* xres, int B, int d,
+                           int add_residual, uint16_t* x_out_bf16, float* y_out_f32,
+                           hipStream_t stream);
 
 }  // namespace pd

@@ -1,13 +1,15 @@
 // The small kernels between the two projections of the parallel block (paper
 // Section 3.4: one LayerNorm per layer feeds both branches, attention and FFN
 // outputs are summed by the fused output projection and added to the residual).
-//   prep     : per-step rotation table cos/sin(positions[b] * base^(-2i/dh)), position check
-//   ln_first : bf16 input -> fp32 residual stream + LayerNorm of layer 0
-//   epi_in   : sum K-split partials of the input projection, apply the per-channel
-//              scale (Section 3.6), rotate q and k, append k/v to the cache,
-//              SwiGLU gate (Section 3.5 names the base-2 Swish)
-//   epi_out  : sum partials of the output projection, scale, add the residual,
-//              LayerNorm for the next layer (or the final bf16 rounding)
+//   prep       : per-step rotation table cos/sin(positions[b] * base^(-2i/dh)), position check
+//   ln_first   : bf16 input -> fp32 residual stream, then LayerNorm of layer 0
+//   epi_in     : sum K-split partials of the input projection, apply the per-channel
+//                scale (Section 3.6), rotate q and k, append k/v to the cache,
+//                SwiGLU gate (Section 3.5 names the base-2 Swish)
+//   residual   : sum partials of the output projection, scale, add the residual
+//   ln         : LayerNorm of the updated residual for the next layer
+// Operands of the projections (LayerNorm output, SwiGLU output) leave these
+// kernels in block fixed point (common.h), one wavefront per 128-element chunk.
 #include "common.h"
 #include "kernels.h"
 
@@ -34,11 +36,15 @@ __global__ __launch_bounds__(128) void prep_kernel(const int32_t* __restrict__ p
     }
 }
 
-// h = gamma * (x - mean) / sqrt(var + eps), population variance, two passes
+// h = gamma * (x - mean) / sqrt(var + eps), population variance, two passes over
+// the row; h is written in block fixed point.  `sum` is this thread's share of
+// sum(x) over the elements tid, tid + 256, ...
 __device__ __forceinline__ void layernorm_row(const float* __restrict__ xrow,
                                               const float* __restrict__ gamma, int d, float eps,
-                                              float sum, uint16_t* __restrict__ hrow, float* red) {
-    const int tid = threadIdx.x;
+                                              float sum, int b, int nd,
+                                              unsigned char* __restrict__ hq,
+                                              float* __restrict__ hs, float* red) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const float mean = block_sum_256(sum, red) / (float)d;
     float sq = 0.f;
     for (int c = tid; c < d; c += 256) {
@@ -47,23 +53,45 @@ __device__ __forceinline__ void layernorm_row(const float* __restrict__ xrow,
     }
     const float var = block_sum_256(sq, red) / (float)d;
     const float rstd = 1.0f / sqrtf(var + eps);
-    for (int c = tid; c < d; c += 256) hrow[c] = to_bf16(gamma[c] * (xrow[c] - mean) * rstd);
+    __syncthreads();  // the row was written by other threads of this block
+    for (int j = wave; j < (d >> 7); j += 4) {
+        const int c = j * QCHUNK + 2 * lane;
+        const f32x2 xv = *reinterpret_cast<const f32x2*>(xrow + c);
+        const f32x2 gv = *reinterpret_cast<const f32x2*>(gamma + c);
+        quantize_chunk_wave(gv.x * (xv.x - mean) * rstd, gv.y * (xv.y - mean) * rstd, lane, nd,
+                            hq + ((size_t)b * d + (size_t)j * QCHUNK) * nd,
+                            hs + (size_t)j * QSCALE_ROWS + b);
+    }
 }
 
 __global__ __launch_bounds__(256) void ln_first_kernel(const uint16_t* __restrict__ x_in,
                                                        const float* __restrict__ gamma, int d,
                                                        float eps, float* __restrict__ xres,
-                                                       uint16_t* __restrict__ h) {
+                                                       unsigned char* __restrict__ hq,
+                                                       float* __restrict__ hs, int nd) {
     __shared__ float red[4];
     const int b = blockIdx.x, tid = threadIdx.x;
     float* xrow = xres + (size_t)b * d;
     float sum = 0.f;
     for (int c = tid; c < d; c += 256) {
         float v = from_bf16(x_in[(size_t)b * d + c]);
-        xrow[c] = v;  // each thread later re-reads only what it wrote itself
+        xrow[c] = v;
         sum += v;
     }
-    layernorm_row(xrow, gamma, d, eps, sum, h + (size_t)b * d, red);
+    layernorm_row(xrow, gamma, d, eps, sum, b, nd, hq, hs, red);
+}
+
+// LayerNorm of the fp32 residual stream for the next layer
+__global__ __launch_bounds__(256) void ln_kernel(const float* __restrict__ xres,
+                                                 const float* __restrict__ gamma, int d, float eps,
+                                                 unsigned char* __restrict__ hq,
+                                                 float* __restrict__ hs, int nd) {
+    __shared__ float red[4];
+    const int b = blockIdx.x, tid = threadIdx.x;
+    const float* xrow = xres + (size_t)b * d;
+    float sum = 0.f;
+    for (int c = tid; c < d; c += 256) sum += xrow[c];
+    layernorm_row(xrow, gamma, d, eps, sum, b, nd, hq, hs, red);
 }
 
 __device__ __forceinline__ float sum_partials(const float* __restrict__ part, int S, size_t stride,
@@ -73,24 +101,52 @@ __device__ __forceinline__ float sum_partials(const float* __restrict__ part, in
     return acc;
 }
 
-// Items per batch row: H*dh/2 q pairs | dh/2 k pairs | dh v elements | F FFN elements.
+// Section A (blockIdx.x < n_blocks_a): one item per thread over H*dh/2 q pairs |
+// dh/2 k pairs | dh v elements.  Section B: one wavefront per 128-element chunk
+// of the SwiGLU output, written in block fixed point into the operand of the
+// output projection (chunks H*dh/128 ... of the row).
 // `part` is in packed column order: q|k|v in place, then 64-column groups of
 // (32 gate, 32 up).  Cache element offsets follow the library block layouts.
 __global__ __launch_bounds__(256) void epi_in_kernel(
     const float* __restrict__ part, int S, const float* __restrict__ scale,
     const float* __restrict__ cs, const int32_t* __restrict__ positions, int B, int H, int dh, int F,
-    int L_ctx, uint16_t* __restrict__ q, uint16_t* __restrict__ kc, uint16_t* __restrict__ vc,
-    uint16_t* __restrict__ act, int act_stride) {
+    int L_ctx, int n_blocks_a, float* __restrict__ q, uint16_t* __restrict__ kc,
+    uint16_t* __restrict__ vc, unsigned char* __restrict__ actq, float* __restrict__ acts, int nd) {
     const int b = blockIdx.y;
-    const int item = blockIdx.x * 256 + threadIdx.x;
     const int half = dh >> 1;
     const int n_q = H * half, n_k = half, n_v = dh;
     const int n_qkv = H * dh + 2 * dh;
     const int N = n_qkv + 2 * F;
+    const int k_out = H * dh + F;
     const size_t stride = (size_t)B * N, rowoff = (size_t)b * N;
+
+    if ((int)blockIdx.x >= n_blocks_a) {
+        const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+        const int j = ((int)blockIdx.x - n_blocks_a) * 4 + wave;  // chunk of the FFN activation
+        if (j >= (F >> 7)) return;
+        const int f = j * QCHUNK + 2 * lane;                      // f and f + 1 share a 32-group
+        const int pcol = n_qkv + (f >> 5) * 64 + (f & 31);
+        float g0 = 0.f, g1 = 0.f, u0 = 0.f, u1 = 0.f;
+        for (int s = 0; s < S; s++) {  // fixed order
+            const float* p = part + (size_t)s * stride + rowoff + pcol;
+            const f32x2 gv = *reinterpret_cast<const f32x2*>(p);
+            const f32x2 uv = *reinterpret_cast<const f32x2*>(p + 32);
+            g0 += gv.x; g1 += gv.y; u0 += uv.x; u1 += uv.y;
+        }
+        g0 *= scale[pcol]; g1 *= scale[pcol + 1];
+        u0 *= scale[pcol + 32]; u1 *= scale[pcol + 33];
+        // swish(g) = g / (1 + e^-g) = g / (1 + 2^(-g log2 e))
+        const float a0 = g0 / (1.0f + __builtin_amdgcn_exp2f(-g0 * 1.4426950408889634f)) * u0;
+        const float a1 = g1 / (1.0f + __builtin_amdgcn_exp2f(-g1 * 1.4426950408889634f)) * u1;
+        const int chunk = (H * dh >> 7) + j;
+        quantize_chunk_wave(a0, a1, lane, nd, actq + ((size_t)b * k_out + (size_t)chunk * QCHUNK) * nd,
+                            acts + (size_t)chunk * QSCALE_ROWS + b);
+        return;
+    }
+
+    const int item = blockIdx.x * 256 + threadIdx.x;
     const int P = positions[b];
     const bool ok = P >= 0 && P < L_ctx;
-
     if (item < n_q + n_k) {
         // rotation pair (i, i + dh/2) of a q head or of k
         const bool is_k = item >= n_q;
@@ -102,9 +158,9 @@ __global__ __launch_bounds__(256) void epi_in_kernel(
         const float cn = cs[((size_t)b * half + i) * 2], sn = cs[((size_t)b * half + i) * 2 + 1];
         const float rlo = lo * cn - hi * sn, rhi = hi * cn + lo * sn;
         if (!is_k) {
-            uint16_t* qrow = q + ((size_t)b * H + head) * dh;
-            qrow[i] = to_bf16(rlo);
-            qrow[i + half] = to_bf16(rhi);
+            float* qrow = q + ((size_t)b * H + head) * dh;
+            qrow[i] = rlo;
+            qrow[i + half] = rhi;
         } else if (ok) {
             const size_t blk = ((size_t)b * (L_ctx >> 5) + (P >> 5)) * 32 * dh;
             const int tt = P & 31;
@@ -123,39 +179,30 @@ __global__ __launch_bounds__(256) void epi_in_kernel(
             vc[blk + ((((size_t)(c >> 5) * 2 + (tt >> 4)) * 2 + ((tt & 7) >> 2)) * 32 + (c & 31)) * 8 +
                4 * ((tt & 15) >> 3) + (tt & 3)] = to_bf16(v);
         }
-    } else if (item < n_q + n_k + n_v + F) {
-        const int f = item - n_q - n_k - n_v;
-        const int pcol = n_qkv + (f >> 5) * 64 + (f & 31);
-        float gt = scale[pcol] * sum_partials(part, S, stride, rowoff + pcol);
-        float up = scale[pcol + 32] * sum_partials(part, S, stride, rowoff + pcol + 32);
-        // swish(g) = g / (1 + e^-g) = g / (1 + 2^(-g log2 e))
-        float sw = gt / (1.0f + __builtin_amdgcn_exp2f(-gt * 1.4426950408889634f));
-        act[(size_t)b * act_stride + H * dh + f] = to_bf16(sw * up);
     }
 }
 
-__global__ __launch_bounds__(256) void epi_out_kernel(const float* __restrict__ part, int S,
-                                                      const float* __restrict__ scale,
-                                                      float* __restrict__ xres,
-                                                      const float* __restrict__ gamma_next, int B,
-                                                      int d, float eps, int add_residual,
-                                                      uint16_t* __restrict__ h,
-                                                      uint16_t* __restrict__ x_out_bf16,
-                                                      float* __restrict__ y_out_f32) {
-    __shared__ float red[4];
-    const int b = blockIdx.x, tid = threadIdx.x;
-    float* xrow = xres + (size_t)b * d;
-    const size_t stride = (size_t)B * d, rowoff = (size_t)b * d;
-    float sum = 0.f;
-    for (int c = tid; c < d; c += 256) {
-        float y = scale[c] * sum_partials(part, S, stride, rowoff + c);
-        float xn = add_residual ? xrow[c] + y : y;
-        xrow[c] = xn;
-        sum += xn;
-        if (x_out_bf16) x_out_bf16[rowoff + c] = to_bf16(xn);
-        if (y_out_f32) y_out_f32[rowoff + c] = xn;
+// x' = [x +] scale * sum_s part[s]   (elementwise; partials summed in index order)
+__global__ __launch_bounds__(256) void residual_kernel(const float* __restrict__ part, int S,
+                                                       const float* __restrict__ scale,
+                                                       float* __restrict__ xres, int B, int d,
+                                                       int add_residual,
+                                                       uint16_t* __restrict__ x_out_bf16,
+                                                       float* __restrict__ y_out_f32) {
+    const int b = blockIdx.y, c = (blockIdx.x * 256 + threadIdx.x) * 4;
+    if (c >= d) return;
+    const size_t stride = (size_t)B * d, off = (size_t)b * d + c;
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    for (int s = 0; s < S; s++) acc += *reinterpret_cast<const f32x4*>(part + (size_t)s * stride + off);
+    const f32x4 sc = *reinterpret_cast<const f32x4*>(scale + c);
+    f32x4 xn = sc * acc;
+    if (add_residual) xn += *reinterpret_cast<const f32x4*>(xres + off);
+    *reinterpret_cast<f32x4*>(xres + off) = xn;
+    if (y_out_f32) *reinterpret_cast<f32x4*>(y_out_f32 + off) = xn;
+    if (x_out_bf16) {
+        uint2 o = {pack_bf16x2(xn.x, xn.y), pack_bf16x2(xn.z, xn.w)};
+        *reinterpret_cast<uint2*>(x_out_bf16 + off) = o;
     }
-    if (gamma_next) layernorm_row(xrow, gamma_next, d, eps, sum, h + rowoff, red);
 }
 
 hipError_t launch_prep(const int32_t* positions, int B, int L_ctx, int dh, float rope_base,
@@ -165,27 +212,38 @@ hipError_t launch_prep(const int32_t* positions, int B, int L_ctx, int dh, float
 }
 
 hipError_t launch_ln_first(const uint16_t* x_in, const float* gamma, int B, int d, float eps,
-                           float* xres, uint16_t* h, hipStream_t stream) {
-    ln_first_kernel<<<dim3(B), dim3(256), 0, stream>>>(x_in, gamma, d, eps, xres, h);
+                           float* xres, void* hq, float* hs, int nd, hipStream_t stream) {
+    ln_first_kernel<<<dim3(B), dim3(256), 0, stream>>>(x_in, gamma, d, eps, xres,
+                                                       reinterpret_cast<unsigned char*>(hq), hs, nd);
+    return hipGetLastError();
+}
+
+hipError_t launch_ln(const float* xres, const float* gamma, int B, int d, float eps, void* hq,
+                     float* hs, int nd, hipStream_t stream) {
+    ln_kernel<<<dim3(B), dim3(256), 0, stream>>>(xres, gamma, d, eps,
+                                                 reinterpret_cast<unsigned char*>(hq), hs, nd);
     return hipGetLastError();
 }
 
 hipError_t launch_epi_in(const float* part, int S, const float* scale, const float* cs,
                          const int32_t* positions, int B, int H, int dh, int F, int L_ctx,
-                         uint16_t* q, void* kc_layer, void* vc_layer, uint16_t* act, int act_stride,
-                         hipStream_t stream) {
-    int items = H * dh / 2 + dh / 2 + dh + F;
-    epi_in_kernel<<<dim3((items + 255) / 256, B), dim3(256), 0, stream>>>(
-        part, S, scale, cs, positions, B, H, dh, F, L_ctx, q, reinterpret_cast<uint16_t*>(kc_layer),
-        reinterpret_cast<uint16_t*>(vc_layer), act, act_stride);
+                         float* q, void* kc_layer, void* vc_layer, void* actq, float* acts,
+                         int nd, hipStream_t stream) {
+    const int items = H * dh / 2 + dh / 2 + dh;
+    const int n_blocks_a = (items + 255) / 256;
+    const int n_blocks_b = (F / 128 + 3) / 4;
+    epi_in_kernel<<<dim3(n_blocks_a + n_blocks_b, B), dim3(256), 0, stream>>>(
+        part, S, scale, cs, positions, B, H, dh, F, L_ctx, n_blocks_a, q,
+        reinterpret_cast<uint16_t*>(kc_layer), reinterpret_cast<uint16_t*>(vc_layer),
+        reinterpret_cast<unsigned char*>(actq), acts, nd);
     return hipGetLastError();
 }
 
-hipError_t launch_epi_out(const float* part, int S, const float* scale, float* xres,
-                          const float* gamma_next, int B, int d, float eps, int add_residual,
-                          uint16_t* h, uint16_t* x_out_bf16, float* y_out_f32, hipStream_t stream) {
-    epi_out_kernel<<<dim3(B), dim3(256), 0, stream>>>(part, S, scale, xres, gamma_next, B, d, eps,
-                                                      add_residual, h, x_out_bf16, y_out_f32);
+hipError_t launch_residual(const float* part, int S, const float* scale, float* xres, int B, int d,
+                           int add_residual, uint16_t* x_out_bf16, float* y_out_f32,
+                           hipStream_t stream) {
+    residual_kernel<<<dim3((d / 4 + 255) / 256, B), dim3(256), 0, stream>>>(
+        part, S, scale, xres, B, d, add_residual, x_out_bf16, y_out_f32);
     return hipGetLastError();
 }
 

@@ -45,10 +45,24 @@ def errors(gpu: np.ndarray, ora: np.ndarray):
     return scaled, rel_l2
 
 
-def report(name, gpu, ora):
+def report(name, gpu, ora, ora64=None):
     scaled, rel = errors(gpu, ora)
     print(f"[parity] {name}: scaled-max {scaled:.3e} rel-L2 {rel:.3e} raw-max "
           f"{float(np.max(np.abs(gpu - ora))):.3e} rms(ora) {float(np.sqrt(np.mean(ora ** 2))):.3e}", flush=True)
+    if gpu.ndim == 2 and gpu.shape[0] > 1:
+        rr = np.linalg.norm(gpu - ora, axis=1) / np.linalg.norm(ora, axis=1)
+        rms = np.sqrt(np.mean(ora ** 2, axis=1, keepdims=True))
+        nrm = np.abs(gpu - ora) / np.maximum(1.0, rms)
+        print(f"[parity]   per-row rel-L2 min {rr.min():.2e} med {np.median(rr):.2e} max {rr.max():.2e}; "
+              f"max |diff|/max(1,row rms) {nrm.max():.3e}", flush=True)
+        sc = np.abs(gpu - ora) / np.maximum(1.0, np.abs(ora))
+        for idx in np.argsort(sc.ravel())[-3:]:
+            r, c = np.unravel_index(idx, sc.shape)
+            extra = f" ora64 {ora64[r, c]:.5f}" if ora64 is not None else ""
+            print(f"[parity]   worst: row {r} col {c} gpu {gpu[r, c]:.5f} ora {ora[r, c]:.5f}{extra}", flush=True)
+        if ora64 is not None:
+            e64 = np.linalg.norm(gpu - ora64) / np.linalg.norm(ora64)
+            print(f"[parity]   rel-L2 vs unrounded fp64 oracle {e64:.3e}", flush=True)
     return scaled, rel
 
 
@@ -130,7 +144,7 @@ def test_attention_vs_oracle(pd, H, dh, L, pos):
     w = Workload("t", 1, 256, H, dh, 256, B, L)
     dec = pd.Decoder(w)
     g = torch.Generator(device="cuda").manual_seed(11 + H)
-    q = (torch.randn(B, H, dh, generator=g, device="cuda") * 1.5).to(torch.bfloat16)
+    q = torch.randn(B, H, dh, generator=g, device="cuda") * 1.5  # fp32, as the input projection leaves it
     k = torch.randn(B, L, dh, generator=g, device="cuda").to(torch.bfloat16)
     v = torch.randn(B, L, dh, generator=g, device="cuda").to(torch.bfloat16)
     p = torch.tensor(pos, dtype=torch.int32, device="cuda")
@@ -144,16 +158,17 @@ def test_attention_vs_oracle(pd, H, dh, L, pos):
     ws = torch.empty(binding.workspace_bytes(dec.desc, B, L), dtype=torch.uint8, device="cuda")
     for bps in (0, 16):
         dec.set_option("attn_blocks_per_split", bps)
-        o = torch.full((B, H * dh), float("nan"), dtype=torch.bfloat16, device="cuda")
+        o = torch.full((B, H * dh), float("nan"), dtype=torch.float32, device="cuda")
         dec.mqa_attend(0, q, kc, vc, p, L, o, ws)
         torch.cuda.synchronize()
-        got = widen(bits_np(o)).reshape(B, H, dh)
+        got = o.cpu().double().numpy().reshape(B, H, dh)
         for b in range(B):
             T = pos[b] + 1
-            want = oracle.attend_mqa(widen(bits_np(q[b])), bits_np(k[b, :T]), bits_np(v[b, :T]))
+            want = oracle.attend_mqa(q[b].cpu().double().numpy(), bits_np(k[b, :T]), bits_np(v[b, :T]))
             assert np.all(np.isfinite(got[b]))
             scaled, rel = errors(got[b], want)
-            assert scaled <= MAX_SCALED and rel <= REL_L2, (b, pos[b], bps, scaled, rel)
+            # K and V are exact; q and the softmax weights carry 16 bits: fp32-grade result
+            assert scaled <= 2e-4 and rel <= 1e-4, (b, pos[b], bps, scaled, rel)
             if T == 1:  # single live slot: every head returns that value row exactly
                 assert np.array_equal(got[b], np.broadcast_to(widen(bits_np(v[b, 0])), (H, dh)))
 
@@ -204,7 +219,7 @@ def run_stack_parity(pd, w, rows=None, poison=True, name=None, positions=None):
     st.dec.check_async(st.workspace)
     gpu = widen(bits_np(out))[rows]
     assert np.all(np.isfinite(gpu))
-    scaled, rel = report(name or w.name, gpu, widen(oracle.f64_to_bf16_bits(x64)))
+    scaled, rel = report(name or w.name, gpu, widen(oracle.f64_to_bf16_bits(x64)), x64)
     check_cache_append(w, st, kcs, vcs, kcs0, vcs0, rows, pos)
     return st, scaled, rel, gpu, x64
 
@@ -218,7 +233,7 @@ def test_decode_step_tiny_workload_raw_tolerance(pd):
 
 @pytest.mark.parametrize("shape", [
     # (layers, d, H, dh, F, B, L, positions): several tiles, ragged batch and ragged lengths
-    (2, 384, 3, 64, 448, 5, 96, [95, 0, 31, 32, 50]),
+    (2, 384, 4, 64, 384, 5, 96, [95, 0, 31, 32, 50]),
     (3, 512, 5, 128, 384, 37, 160, None),
     (1, 1024, 32, 256, 1024, 70, 64, None),
 ])
