@@ -71,8 +71,8 @@ def main():
     ap.add_argument("--workload", default="c3_62b")
     ap.add_argument("--no-graph", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--split-in", type=int, default=0)
-    ap.add_argument("--split-out", type=int, default=0)
+    ap.add_argument("--gemm-wg-in", type=int, default=0)
+    ap.add_argument("--gemm-wg-out", type=int, default=0)
     ap.add_argument("--attn-bps", type=int, default=0)
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -88,7 +88,7 @@ def main():
     w = WORKLOADS[args.workload]
     t_setup = time.perf_counter()
     st = harness.DeviceStack(w)
-    for name, val in (("split_in", args.split_in), ("split_out", args.split_out),
+    for name, val in (("gemm_workgroups_in", args.gemm_wg_in), ("gemm_workgroups_out", args.gemm_wg_out),
                       ("attn_blocks_per_split", args.attn_bps)):
         if val:
             st.dec.set_option(name, val)

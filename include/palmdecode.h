@@ -102,9 +102,12 @@ pd_status pd_workspace_bytes(const pd_model_desc* desc, int32_t B, int32_t L_ctx
  * an optional captured graph). */
 pd_status pd_create(const pd_model_desc* desc, pd_handle** out);
 pd_status pd_destroy(pd_handle* h);
-/* Tuning knobs, e.g. "split_in", "split_out" (K-splits of the two projections,
- * 0 = automatic), "attn_blocks_per_split" (32-token blocks per attention
- * workgroup, 0 = automatic).  Unknown names return PD_ERR_RANGE. */
+/* Tuning knobs: "gemm_workgroups_in", "gemm_workgroups_out" (workgroups that
+ * share the weight matrix of the input / output projection, 0 = automatic: one
+ * per compute unit), "attn_blocks_per_split" (32-token blocks per attention
+ * workgroup, 0 = automatic), "act_digits" (2 or 3 int8 digit planes per
+ * projection operand), "profile_kernel" (see pd_profile_read).  Unknown names
+ * return PD_ERR_RANGE. */
 pd_status pd_set_option(pd_handle* h, const char* name, int32_t value);
 
 /* Event timing of one kernel class, for the roofline report.  Option
@@ -180,11 +183,13 @@ pd_status pd_check_async(pd_handle* h, void* workspace, void* stream);
 /* out[b][n] = s[n] * sum_k a[b][k] * w[k][n]   (Section 3.6 weight-only int8)
  *   packed_w from pd_pack_matrix, scale [N] fp32 device, a [B][K] bf16 device,
  *   out [B][N] fp32 device, B <= 256.  workspace >= pd_qgemm_workspace_bytes().
+ *   `workgroups` (0 = automatic, else 1..4096) is the number of workgroups the
+ *   matrix is shared between; the result is bit-reproducible for a given value.
  *   The activations are converted to the library's 3-digit block fixed point
  *   (23 bits relative to each 128-element chunk's maximum) before the product. */
 pd_status pd_qgemm_workspace_bytes(int32_t B, int32_t K, int32_t N, size_t* bytes);
 pd_status pd_qgemm(const void* packed_w, const float* scale, const uint16_t* a, int32_t B,
-                   int32_t K, int32_t N, float* out, int32_t k_splits, void* workspace,
+                   int32_t K, int32_t N, float* out, int32_t workgroups, void* workspace,
                    size_t workspace_bytes, void* stream);
 
 /* Multiquery attention of one layer over the library-layout cache (Section 3.3):

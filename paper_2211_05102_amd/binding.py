@@ -112,12 +112,12 @@ def pack_matrix(w: torch.Tensor, packed: torch.Tensor, stream=None) -> None:
 
 
 def qgemm(packed_w: torch.Tensor, scale: torch.Tensor, a: torch.Tensor, N: int, out: torch.Tensor,
-          workspace: torch.Tensor, k_splits: int = 0, stream=None) -> None:
+          workspace: torch.Tensor, workgroups: int = 0, stream=None) -> None:
     B, K = a.shape
     assert a.dtype == torch.bfloat16 and a.is_contiguous() and scale.dtype == torch.float32
     assert out.dtype == torch.float32 and out.shape == (B, N) and out.is_contiguous()
     _check(lib().pd_qgemm(_ptr(packed_w), _ptr(scale), _ptr(a), ctypes.c_int32(B), ctypes.c_int32(K),
-                          ctypes.c_int32(N), _ptr(out), ctypes.c_int32(k_splits), _ptr(workspace),
+                          ctypes.c_int32(N), _ptr(out), ctypes.c_int32(workgroups), _ptr(workspace),
                           ctypes.c_size_t(workspace.numel() * workspace.element_size()), _stream(stream)))
 
 

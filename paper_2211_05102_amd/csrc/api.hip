@@ -80,7 +80,22 @@ int auto_bps(int B, int L_ctx) {
     return (int)v;
 }
 
-// workspace carving; sized for the largest split counts so options never overflow it
+// Launch plan of the two projections for batch B: workgroups (stream-K shares of the
+// weight matrix) and partial-sum slots per tile.  Fixed by the shape alone -- the
+// chip this library is written for has 256 compute units -- so results do not
+// depend on where the code runs and the workspace can be sized on the host.
+constexpr int PD_NUM_CUS = 256;
+struct GemmPlan {
+    int G_in, slots_in, G_out, slots_out;
+};
+GemmPlan gemm_plan(const Shape& s, int B, int g_in_opt, int g_out_opt) {
+    GemmPlan p;
+    pd::qgemm_plan(B, s.d, s.n_in, g_in_opt > 0 ? g_in_opt : PD_NUM_CUS, &p.G_in, &p.slots_in);
+    pd::qgemm_plan(B, s.k_out, s.d, g_out_opt > 0 ? g_out_opt : PD_NUM_CUS, &p.G_out, &p.slots_out);
+    return p;
+}
+
+// workspace carving; sized for the largest slot counts so options never overflow it
 struct Workspace {
     size_t flag, cs, xres, h, hs, part_in, q, act, acts, opart, ml, part_out, total;
 };
@@ -93,7 +108,7 @@ Workspace workspace_layout(const Shape& s, int B, int L_ctx) {
     w.xres = o; o += align256((size_t)B * s.d * 4);
     w.h = o; o += align256((size_t)B * s.d * 3);                    // digit planes of LN(x)
     w.hs = o; o += align256((size_t)(s.d / 128) * 256 * 4);         // their scales [chunk][256]
-    w.part_in = o; o += align256((size_t)PD_MAX_SPLITS * B * s.n_in * 4);
+    w.part_in = o; o += align256((size_t)PD_MAX_SPLITS * B * s.n_in * 4);  // slots <= PD_MAX_SPLITS
     w.q = o; o += align256((size_t)B * s.H * s.dh * 4);
     w.act = o; o += align256((size_t)B * s.k_out * 3);              // digit planes of [o | a]
     w.acts = o; o += align256((size_t)(s.k_out / 128) * 256 * 4);
@@ -111,7 +126,7 @@ size_t kv_layer_elems(const Shape& s, int B, int L_ctx) { return (size_t)B * L_c
 struct pd_handle {
     pd_model_desc desc;
     Shape s;
-    int opt_split_in = 0, opt_split_out = 0, opt_bps = 0;
+    int opt_g_in = 0, opt_g_out = 0, opt_bps = 0;  // 0 = automatic
     int act_digits = 3;  // int8 digit planes per projection operand
     hipGraph_t graph = nullptr;
     hipGraphExec_t graph_exec = nullptr;
@@ -175,8 +190,16 @@ pd_status run_layers(pd_handle* h, const StepArgs& a, hipStream_t st) {
     float* ml = reinterpret_cast<float*>(a.ws + w.ml);
     float* part_out = reinterpret_cast<float*>(a.ws + w.part_out);
 
-    const int S_in = h->opt_split_in > 0 ? h->opt_split_in : pd::qgemm_auto_splits(B, s.d, s.n_in);
-    const int S_out = h->opt_split_out > 0 ? h->opt_split_out : pd::qgemm_auto_splits(B, s.k_out, s.d);
+    const GemmPlan gp = gemm_plan(s, B, h->opt_g_in, h->opt_g_out);
+    const pd::SkqPlan pl_in = pd::qgemm_skq(B, s.d, s.n_in, gp.G_in);
+    const pd::SkqPlan pl_out = pd::qgemm_skq(B, s.k_out, s.d, gp.G_out);
+    // scale blocks of the projection operands (chunks of 128 that share one
+    // power-of-two scale): LayerNorm output = one scale per row; attention output
+    // and SwiGLU output = blocks of blk_o and blk_a chunks
+    const int c_in = s.d / 128, c_attn = s.H * s.dh / 128, c_ffn = s.F / 128;
+    const int blk_ln = c_in < 1024 ? c_in : 1024;
+    const int blk_o = c_attn < 16 ? c_attn : 16;
+    const int blk_a = c_ffn < 64 ? c_ffn : 64;
     const int bps = h->opt_bps > 0 ? h->opt_bps : auto_bps(B, a.L_ctx);
     const int nd = h->act_digits;
     const size_t kv_layer_bytes = kv_layer_elems(s, B, a.L_ctx) * 2;
@@ -192,22 +215,23 @@ pd_status run_layers(pd_handle* h, const StepArgs& a, hipStream_t st) {
         if (i == 0)
             PD_TRY_HIP(pd::launch_ln_first(a.x_in, gamma, B, s.d, h->desc.ln_eps, xres, hq, hs, nd, st), "ln_first");
         prof_mark(h, PROF_QGEMM_IN, st);
-        PD_TRY_HIP(pd::launch_qgemm(L + pl.w_in, hq, hs, part_in, B, s.d, s.n_in, S_in, nd, st), "qgemm_in");
+        PD_TRY_HIP(pd::launch_qgemm(L + pl.w_in, hq, hs, part_in, B, s.d, s.n_in, gp.G_in, 0, 1, blk_ln, nd, st), "qgemm_in");
         prof_mark(h, PROF_QGEMM_IN, st);
         prof_mark(h, PROF_EPI_IN, st);
-        PD_TRY_HIP(pd::launch_epi_in(part_in, S_in, s_in, cs, a.positions, B, s.H, s.dh, s.F, a.L_ctx, q,
-                                     kc, vc, actq, acts, nd, st), "epi_in");
+        PD_TRY_HIP(pd::launch_epi_in(part_in, pl_in, s_in, cs, a.positions, B, s.H, s.dh, s.F, a.L_ctx, q,
+                                     kc, vc, actq, acts, blk_a, nd, st), "epi_in");
         prof_mark(h, PROF_EPI_IN, st);
         prof_mark(h, PROF_ATTEND, st);
         PD_TRY_HIP(pd::launch_mqa_attend(q, kc, vc, a.positions, B, s.H, s.dh, a.L_ctx, bps, opart, ml,
-                                         nullptr, actq, acts, s.k_out, nd, st), "mqa_attend");
+                                         nullptr, actq, acts, s.k_out, blk_o, nd, st), "mqa_attend");
         prof_mark(h, PROF_ATTEND, st);
         prof_mark(h, PROF_QGEMM_OUT, st);
-        PD_TRY_HIP(pd::launch_qgemm(L + pl.w_out, actq, acts, part_out, B, s.k_out, s.d, S_out, nd, st), "qgemm_out");
+        PD_TRY_HIP(pd::launch_qgemm(L + pl.w_out, actq, acts, part_out, B, s.k_out, s.d, gp.G_out, c_attn, blk_o,
+                                    blk_a, nd, st), "qgemm_out");
         prof_mark(h, PROF_QGEMM_OUT, st);
         const bool last = i == a.n_run - 1;
         prof_mark(h, PROF_EPI_OUT, st);
-        PD_TRY_HIP(pd::launch_residual(part_out, S_out, s_out, xres, B, s.d, a.add_residual,
+        PD_TRY_HIP(pd::launch_residual(part_out, pl_out, s_out, xres, B, s.d, a.add_residual,
                                        last ? a.x_out_bf16 : nullptr, last ? a.y_out_f32 : nullptr, st),
                    "residual");
         if (!last) {
@@ -315,11 +339,9 @@ pd_status pd_destroy(pd_handle* h) {
 
 pd_status pd_set_option(pd_handle* h, const char* name, int32_t value) {
     if (!h || !name) return fail(PD_ERR_NULL, "NULL argument");
-    if (!strcmp(name, "split_in") || !strcmp(name, "split_out")) {
-        if (value < 0 || value > PD_MAX_SPLITS) return fail(PD_ERR_RANGE, "split count must be in 0..16");
-        int K = !strcmp(name, "split_in") ? h->s.d : h->s.k_out;
-        if (value > K / 128) return fail(PD_ERR_RANGE, "more splits than 128-row chunks");
-        (!strcmp(name, "split_in") ? h->opt_split_in : h->opt_split_out) = value;
+    if (!strcmp(name, "gemm_workgroups_in") || !strcmp(name, "gemm_workgroups_out")) {
+        if (value < 0 || value > 4096) return fail(PD_ERR_RANGE, "workgroup count must be in 0..4096");
+        (!strcmp(name, "gemm_workgroups_in") ? h->opt_g_in : h->opt_g_out) = value;
         return PD_OK;
     }
     if (!strcmp(name, "attn_blocks_per_split")) {
@@ -455,7 +477,7 @@ pd_status pd_qgemm_workspace_bytes(int32_t B, int32_t K, int32_t N, size_t* byte
 }
 
 pd_status pd_qgemm(const void* packed_w, const float* scale, const uint16_t* a, int32_t B, int32_t K,
-                   int32_t N, float* out, int32_t k_splits, void* workspace, size_t workspace_bytes,
+                   int32_t N, float* out, int32_t workgroups, void* workspace, size_t workspace_bytes,
                    void* stream) {
     if (!packed_w || !scale || !a || !out || !workspace) return fail(PD_ERR_NULL, "NULL device pointer");
     size_t need = 0;
@@ -464,16 +486,18 @@ pd_status pd_qgemm(const void* packed_w, const float* scale, const uint16_t* a, 
     if (workspace_bytes < need) return fail(PD_ERR_WORKSPACE, "workspace too small");
     if (!aligned(packed_w, 256) || !aligned(workspace, 256) || !aligned(a, 16) || !aligned(out, 16))
         return fail(PD_ERR_ALIGN, "misaligned device pointer");
-    if (k_splits < 0 || k_splits > PD_MAX_SPLITS || k_splits > K / 128) return fail(PD_ERR_RANGE, "k_splits out of range");
-    const int S = k_splits > 0 ? k_splits : pd::qgemm_auto_splits(B, K, N);
+    if (workgroups < 0 || workgroups > 4096) return fail(PD_ERR_RANGE, "workgroups out of range");
+    int G = 0, slots = 0;
+    pd::qgemm_plan(B, K, N, workgroups > 0 ? workgroups : PD_NUM_CUS, &G, &slots);
     hipStream_t st = static_cast<hipStream_t>(stream);
     unsigned char* wsb = static_cast<unsigned char*>(workspace);
     float* part = reinterpret_cast<float*>(wsb);
     unsigned char* qa = wsb + align256((size_t)PD_MAX_SPLITS * B * N * 4);
     float* qs = reinterpret_cast<float*>(qa + align256((size_t)B * K * 3));
     PD_TRY_HIP(pd::launch_quantize_bf16(a, qa, qs, B, K, 3, st), "quantize");
-    PD_TRY_HIP(pd::launch_qgemm(packed_w, qa, qs, part, B, K, N, S, 3, st), "qgemm");
-    PD_TRY_HIP(pd::launch_qgemm_reduce(part, scale, out, B, N, S, st), "qgemm_reduce");
+    // the test quantiser gives every 128-element chunk its own scale: blocks of one chunk
+    PD_TRY_HIP(pd::launch_qgemm(packed_w, qa, qs, part, B, K, N, G, 0, 1, 1, 3, st), "qgemm");
+    PD_TRY_HIP(pd::launch_qgemm_reduce(part, scale, out, B, K, N, G, st), "qgemm_reduce");
     return PD_OK;
 }
 
@@ -496,7 +520,7 @@ pd_status pd_mqa_attend(pd_handle* h, int32_t layer, const float* q, const void*
     PD_TRY_HIP(pd::launch_mqa_attend(q, static_cast<const unsigned char*>(k_cache) + off,
                                      static_cast<const unsigned char*>(v_cache) + off, positions, B, s.H,
                                      s.dh, L_ctx, bps, reinterpret_cast<float*>(ws + w.opart),
-                                     reinterpret_cast<float*>(ws + w.ml), o, nullptr, nullptr, s.k_out,
+                                     reinterpret_cast<float*>(ws + w.ml), o, nullptr, nullptr, s.k_out, 1,
                                      h->act_digits, static_cast<hipStream_t>(stream)), "mqa_attend");
     return PD_OK;
 }

@@ -224,43 +224,64 @@ __global__ __launch_bounds__(256) void mqa_attend_kernel(
 }
 
 // o[b][h*dh + c] = sum_s w_s O_s[c] / sum_s w_s l_s,  w_s = 2^(m_s - max m), splits in index order.
-// One wavefront per 128-element chunk of the row (two adjacent channels per lane);
-// the result goes out as fp32 (`o`) and/or in block fixed point as the first
+// One workgroup per scale block of the row (blk_o chunks of 128 elements, at most
+// 16); each wave takes every fourth chunk, two adjacent channels per lane.  The
+// result goes out as fp32 (`o`) and/or in block fixed point as the first
 // H*dh/128 chunks of the output projection's operand (`actq`, `acts`).
 __global__ __launch_bounds__(256) void mqa_combine_kernel(
     const float* __restrict__ opart, const float* __restrict__ ml,
     const int32_t* __restrict__ positions, int H, int dh, int L_ctx, int bps, int nsplit,
     float* __restrict__ o, unsigned char* __restrict__ actq, float* __restrict__ acts,
-    int k_out, int nd) {
+    int k_out, int blk_o, int nd) {
+    __shared__ float red[4];
     const int b = blockIdx.y;
     const int P = positions[b];
     if (P < 0 || P >= L_ctx) return;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int j = blockIdx.x * 4 + wave;
-    if (j >= (H * dh >> 7)) return;
+    const int c_lo = blockIdx.x * blk_o;
+    const int c_hi = c_lo + blk_o < (H * dh >> 7) ? c_lo + blk_o : (H * dh >> 7);
     const int live = ((P >> 5) + bps) / bps;  // ceil(nblk / bps), nblk = P/32 + 1
-    const int idx = j * QCHUNK + 2 * lane;     // idx and idx + 1 lie in the same head
-    const int h = idx / dh, c = idx - h * dh;
-    const size_t row0 = (size_t)b * nsplit * H + h;
-    float m_all = -INFINITY;
-    for (int s = 0; s < live; s++) m_all = fmaxf(m_all, ml[(row0 + (size_t)s * H) * 2]);
-    float n0 = 0.f, n1 = 0.f, den = 0.f;
-    for (int s = 0; s < live; s++) {
-        const size_t row = row0 + (size_t)s * H;
-        const float w = __builtin_amdgcn_exp2f(ml[row * 2] - m_all);
-        den += w * ml[row * 2 + 1];
-        const f32x2 ov = *reinterpret_cast<const f32x2*>(opart + row * dh + c);
-        n0 += w * ov.x;
-        n1 += w * ov.y;
+    float o0[4], o1[4], mx = 0.f;
+#pragma unroll
+    for (int k = 0; k < 4; k++) {
+        const int j = c_lo + wave + 4 * k;
+        o0[k] = o1[k] = 0.f;
+        if (j < c_hi) {
+            const int idx = j * QCHUNK + 2 * lane;  // idx and idx + 1 lie in the same head
+            const int h = idx / dh, c = idx - h * dh;
+            const size_t row0 = (size_t)b * nsplit * H + h;
+            float m_all = -INFINITY;
+            for (int s = 0; s < live; s++) m_all = fmaxf(m_all, ml[(row0 + (size_t)s * H) * 2]);
+            float n0 = 0.f, n1 = 0.f, den = 0.f;
+            for (int s = 0; s < live; s++) {
+                const size_t row = row0 + (size_t)s * H;
+                const float w = __builtin_amdgcn_exp2f(ml[row * 2] - m_all);
+                den += w * ml[row * 2 + 1];
+                const f32x2 ov = *reinterpret_cast<const f32x2*>(opart + row * dh + c);
+                n0 += w * ov.x;
+                n1 += w * ov.y;
+            }
+            o0[k] = n0 / den;
+            o1[k] = n1 / den;
+            mx = fmaxf(mx, fmaxf(fabsf(o0[k]), fabsf(o1[k])));
+            if (o) {
+                const f32x2 ov = {o0[k], o1[k]};
+                *reinterpret_cast<f32x2*>(o + (size_t)b * H * dh + idx) = ov;
+            }
+        }
     }
-    const float o0 = n0 / den, o1 = n1 / den;
-    if (o) {
-        const f32x2 ov = {o0, o1};
-        *reinterpret_cast<f32x2*>(o + (size_t)b * H * dh + idx) = ov;
+    if (!actq) return;
+    const float s = qscale_from_max(block_max_256(mx, red), nd);
+    const float inv = 1.0f / s;
+#pragma unroll
+    for (int k = 0; k < 4; k++) {
+        const int j = c_lo + wave + 4 * k;
+        if (j < c_hi) {
+            quantize_pair_store(o0[k], o1[k], inv, nd, lane,
+                                actq + ((size_t)b * k_out + (size_t)j * QCHUNK) * nd);
+            if (lane == 0) acts[(size_t)j * QSCALE_ROWS + b] = s;
+        }
     }
-    if (actq)
-        quantize_chunk_wave(o0, o1, lane, nd, actq + ((size_t)b * k_out + (size_t)j * QCHUNK) * nd,
-                            acts + (size_t)j * QSCALE_ROWS + b);
 }
 
 // canonical [B][L_ctx][dh]  <->  library block layout, one element per thread
@@ -290,7 +311,8 @@ __global__ __launch_bounds__(256) void kv_convert_kernel(const uint16_t* __restr
 hipError_t launch_mqa_attend(const float* q, const void* kc_layer, const void* vc_layer,
                              const int32_t* positions, int B, int H, int dh, int L_ctx, int bps,
                              float* opart, float* ml, float* o, void* actq, float* acts,
-                             int k_out, int nd, hipStream_t stream) {
+                             int k_out, int blk_o, int nd, hipStream_t stream) {
+    if (blk_o < 1 || blk_o > 16) return hipErrorInvalidValue;
     const int nblk_cap = L_ctx / 32;
     const int nsplit = (nblk_cap + bps - 1) / bps;
     const float scale_log2e = 1.4426950408889634f / sqrtf((float)dh);
@@ -310,9 +332,9 @@ hipError_t launch_mqa_attend(const float* q, const void* kc_layer, const void* v
         return hipErrorInvalidValue;
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    mqa_combine_kernel<<<dim3((H * dh / 128 + 3) / 4, B), block, 0, stream>>>(
+    mqa_combine_kernel<<<dim3((H * dh / 128 + blk_o - 1) / blk_o, B), block, 0, stream>>>(
         opart, ml, positions, H, dh, L_ctx, bps, nsplit, o, reinterpret_cast<unsigned char*>(actq),
-        acts, k_out, nd);
+        acts, k_out, blk_o, nd);
     return hipGetLastError();
 }
 

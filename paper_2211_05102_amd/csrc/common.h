@@ -15,6 +15,23 @@ typedef int i32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int WAVE = 64;
 
+// ---- deterministic stream-K bookkeeping (see qgemm.hip) ------------------------
+// U units are spread over G workgroups, workgroup g taking [g*U/G, (g+1)*U/G).
+// Workgroup that owns unit u:
+__host__ __device__ inline int skq_owner(long long u, long long U, int G) {
+    return (int)(((u + 1) * G - 1) / U);
+}
+// Partial slots written for tile t (C units per tile, T tiles): one per workgroup
+// whose range meets the tile, in workgroup order.
+__host__ __device__ inline int skq_slots(int t, int C, int T, int G) {
+    const long long U = (long long)T * C;
+    return skq_owner((long long)(t + 1) * C - 1, U, G) - skq_owner((long long)t * C, U, G) + 1;
+}
+// How the consumer of a projection finds its partial sums.
+struct SkqPlan {
+    int tile_cols, C, T, G;
+};
+
 // round-to-nearest-even fp32 -> bf16 bit pattern (v_cvt_pk_bf16_f32 on gfx950)
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
     f32x2 p = {lo, hi};
@@ -45,7 +62,9 @@ __device__ __forceinline__ float wave_max(float v) {
 
 // ---- block fixed-point activations ------------------------------------------
 // The operands of the two projections are stored as ND (2 or 3) int8 digit
-// planes with one power-of-two scale per (row, 128-element chunk):
+// planes with one power-of-two scale per (row, 128-element chunk); producers
+// give all chunks of a larger "scale block" the same scale so that the consumer
+// can keep its exact int32 sums running across the block:
 //     value ~= scale * sum_p 256^(ND-1-p) * d_p,   d_0 in [-127,127], others in [-128,127]
 // i.e. 8*ND - 1 bits + sign relative to the chunk maximum (ND = 3: fp32-grade),
 // which the int8 MFMA multiplies with the int8 weights exactly (int32 sums).
@@ -56,23 +75,26 @@ __device__ __forceinline__ float wave_max(float v) {
 constexpr int QCHUNK = 128;
 constexpr int QSCALE_ROWS = 256;
 
-// One wavefront quantises one chunk: lane holds elements 2*lane and 2*lane+1.
-__device__ __forceinline__ void quantize_chunk_wave(float v0, float v1, int lane, int nd,
-                                                    unsigned char* __restrict__ row_chunk,
-                                                    float* __restrict__ scale_slot) {
-    const float mx = wave_max(fmaxf(fabsf(v0), fabsf(v1)));
+// Power-of-two scale for a block whose largest magnitude is mx: the smallest
+// 2^e with mx / 2^e <= 127 * 256^(nd-1).
+__device__ __forceinline__ float qscale_from_max(float mx, int nd) {
     const int top_bits = 8 * (nd - 1);                  // weight of the top digit = 2^top_bits
     const float nmax = (float)(127 << top_bits);        // 32512 or 8323072
     float s = 1.0f;
     if (mx >= 1e-30f && mx < 1e30f) {
-        // smallest power of two with mx / s <= nmax
         const int fl = (int)((__float_as_uint(mx) >> 23) & 0xff) - 127;  // floor(log2 mx)
         s = __uint_as_float((uint32_t)(fl - (top_bits + 6) + 127) << 23);  // nmax < 2^(top_bits+7)
         if (mx > nmax * s) s *= 2.0f;
     }
-    const float inv = 1.0f / s;  // exact
-    const int lim = 127 << top_bits;
-    int n0 = (int)rintf(v0 * inv), n1 = (int)rintf(v1 * inv);
+    return s;
+}
+
+// Lane `lane` of a wavefront writes the digits of elements 2*lane and 2*lane+1 of
+// one 128-element chunk (row_chunk points at the chunk's plane 0).
+__device__ __forceinline__ void quantize_pair_store(float v0, float v1, float inv_scale, int nd,
+                                                    int lane, unsigned char* __restrict__ row_chunk) {
+    const int lim = 127 << (8 * (nd - 1));
+    int n0 = (int)rintf(v0 * inv_scale), n1 = (int)rintf(v1 * inv_scale);
     n0 = n0 > lim ? lim : (n0 < -lim ? -lim : n0);  // only NaN/inf inputs get here
     n1 = n1 > lim ? lim : (n1 < -lim ? -lim : n1);
     // digits from the least significant up: floor division keeps every lower digit in [-128,127]
@@ -91,6 +113,15 @@ __device__ __forceinline__ void quantize_chunk_wave(float v0, float v1, int lane
         *(reinterpret_cast<uint16_t*>(row_chunk + p * QCHUNK) + lane) =
             (uint16_t)((d0 & 0xff) | ((d1 & 0xff) << 8));
     }
+}
+
+// One wavefront quantises one chunk with its own scale (lane holds elements
+// 2*lane and 2*lane+1).
+__device__ __forceinline__ void quantize_chunk_wave(float v0, float v1, int lane, int nd,
+                                                    unsigned char* __restrict__ row_chunk,
+                                                    float* __restrict__ scale_slot) {
+    const float s = qscale_from_max(wave_max(fmaxf(fabsf(v0), fabsf(v1))), nd);
+    quantize_pair_store(v0, v1, 1.0f / s, nd, lane, row_chunk);
     if (lane == 0) *scale_slot = s;
 }
 
@@ -107,6 +138,15 @@ __device__ __forceinline__ float block_sum_256(float v, float* red) {
     if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
     __syncthreads();
     return (red[0] + red[1]) + (red[2] + red[3]);
+}
+
+// Max over a 256-thread block; every thread gets the result.  `red` = 4 floats of LDS.
+__device__ __forceinline__ float block_max_256(float v, float* red) {
+    v = wave_max(v);
+    __syncthreads();  // protects `red` against the previous use
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+    __syncthreads();
+    return fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
 }
 
 }  // namespace pd

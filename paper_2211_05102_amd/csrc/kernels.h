@@ -3,6 +3,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "common.h"
+
 #define PD_MAX_SPLITS 16          // K-splits of a projection
 #define PD_MIN_BLOCKS_PER_SPLIT 4 // 32-token blocks per attention workgroup, lower bound
 
@@ -10,23 +12,25 @@ namespace pd {
 
 // ---- qgemm.hip
 void qgemm_config(int B, int* bm, int* ns, int* tile_cols);
-int qgemm_auto_splits(int B, int K, int N);
+void qgemm_plan(int B, int K, int N, int num_cus, int* G, int* slots);
+SkqPlan qgemm_skq(int B, int K, int N, int G);
 hipError_t launch_qgemm(const void* wp, const void* qa, const float* scale_t, float* part, int B,
-                        int K, int N, int S, int nd, hipStream_t stream);
+                        int K, int N, int G, int c_split, int blk0, int blk1, int nd,
+                        hipStream_t stream);
 hipError_t launch_quantize_bf16(const uint16_t* a, void* qa, float* scale_t, int B, int K, int nd,
                                 hipStream_t stream);
 hipError_t launch_pack_matrix(const int8_t* w, void* dst, int K, int N, int mode, int n_qkv, int F,
                               hipStream_t stream);
 hipError_t launch_pack_vector(const uint16_t* src, float* dst, int N, int mode, int n_qkv, int F,
                               hipStream_t stream);
-hipError_t launch_qgemm_reduce(const float* part, const float* scale, float* out, int B, int N,
-                               int S, hipStream_t stream);
+hipError_t launch_qgemm_reduce(const float* part, const float* scale, float* out, int B, int K,
+                               int N, int G, hipStream_t stream);
 
 // ---- attention.hip
 hipError_t launch_mqa_attend(const float* q, const void* kc_layer, const void* vc_layer,
                              const int32_t* positions, int B, int H, int dh, int L_ctx, int bps,
                              float* opart, float* ml, float* o, void* actq, float* acts,
-                             int k_out, int nd, hipStream_t stream);
+                             int k_out, int blk_o, int nd, hipStream_t stream);
 hipError_t launch_kv_convert(const void* src, void* dst, int B, int L_ctx, int dh, int is_v,
                              int to_library, hipStream_t stream);
 
@@ -37,12 +41,12 @@ hipError_t launch_ln_first(const uint16_t* x_in, const float* gamma, int B, int 
                            float* xres, void* hq, float* hs, int nd, hipStream_t stream);
 hipError_t launch_ln(const float* xres, const float* gamma, int B, int d, float eps, void* hq,
                      float* hs, int nd, hipStream_t stream);
-hipError_t launch_epi_in(const float* part, int S, const float* scale, const float* cs,
+hipError_t launch_epi_in(const float* part, SkqPlan pl, const float* scale, const float* cs,
                          const int32_t* positions, int B, int H, int dh, int F, int L_ctx,
                          float* q, void* kc_layer, void* vc_layer, void* actq, float* acts,
-                         int nd, hipStream_t stream);
-hipError_t launch_residual(const float* part, int S, const float* scale, float* xres, int B, int d,
-                           int add_residual, uint16_t* x_out_bf16, float* y_out_f32,
+                         int blk_a, int nd, hipStream_t stream);
+hipError_t launch_residual(const float* part, SkqPlan pl, const float* scale, float* xres, int B,
+                           int d, int add_residual, uint16_t* x_out_bf16, float* y_out_f32,
                            hipStream_t stream);
 
 }  // namespace pd

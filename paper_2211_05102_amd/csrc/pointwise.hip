@@ -37,7 +37,8 @@ __global__ __launch_bounds__(128) void prep_kernel(const int32_t* __restrict__ p
 }
 
 // h = gamma * (x - mean) / sqrt(var + eps), population variance, two passes over
-// the row; h is written in block fixed point.  `sum` is this thread's share of
+// the row; h is written in block fixed point with ONE scale for the whole row
+// (a LayerNorm output has no outlying chunk).  `sum` is this thread's share of
 // sum(x) over the elements tid, tid + 256, ...
 __device__ __forceinline__ void layernorm_row(const float* __restrict__ xrow,
                                               const float* __restrict__ gamma, int d, float eps,
@@ -53,14 +54,17 @@ __device__ __forceinline__ void layernorm_row(const float* __restrict__ xrow,
     }
     const float var = block_sum_256(sq, red) / (float)d;
     const float rstd = 1.0f / sqrtf(var + eps);
-    __syncthreads();  // the row was written by other threads of this block
+    float mx = 0.f;
+    for (int c = tid; c < d; c += 256) mx = fmaxf(mx, fabsf(gamma[c] * (xrow[c] - mean) * rstd));
+    const float s = qscale_from_max(block_max_256(mx, red), nd);
+    const float inv = 1.0f / s;
     for (int j = wave; j < (d >> 7); j += 4) {
         const int c = j * QCHUNK + 2 * lane;
         const f32x2 xv = *reinterpret_cast<const f32x2*>(xrow + c);
         const f32x2 gv = *reinterpret_cast<const f32x2*>(gamma + c);
-        quantize_chunk_wave(gv.x * (xv.x - mean) * rstd, gv.y * (xv.y - mean) * rstd, lane, nd,
-                            hq + ((size_t)b * d + (size_t)j * QCHUNK) * nd,
-                            hs + (size_t)j * QSCALE_ROWS + b);
+        quantize_pair_store(gv.x * (xv.x - mean) * rstd, gv.y * (xv.y - mean) * rstd, inv, nd, lane,
+                            hq + ((size_t)b * d + (size_t)j * QCHUNK) * nd);
+        if (lane == 0) hs[(size_t)j * QSCALE_ROWS + b] = s;
     }
 }
 
@@ -78,6 +82,7 @@ __global__ __launch_bounds__(256) void ln_first_kernel(const uint16_t* __restric
         xrow[c] = v;
         sum += v;
     }
+    __syncthreads();  // the row is re-read with a different thread mapping below
     layernorm_row(xrow, gamma, d, eps, sum, b, nd, hq, hs, red);
 }
 
@@ -94,24 +99,29 @@ __global__ __launch_bounds__(256) void ln_kernel(const float* __restrict__ xres,
     layernorm_row(xrow, gamma, d, eps, sum, b, nd, hq, hs, red);
 }
 
-__device__ __forceinline__ float sum_partials(const float* __restrict__ part, int S, size_t stride,
-                                              size_t off) {
+// sum over the partial slots of the tile that holds packed column `col` (fixed order)
+__device__ __forceinline__ float sum_partials(const float* __restrict__ part, const SkqPlan& pl,
+                                              size_t stride, size_t off, int col) {
+    const int ns = skq_slots(col / pl.tile_cols, pl.C, pl.T, pl.G);
     float acc = 0.f;
-    for (int s = 0; s < S; s++) acc += part[(size_t)s * stride + off];  // fixed order
+    for (int s = 0; s < ns; s++) acc += part[(size_t)s * stride + off];
     return acc;
 }
 
 // Section A (blockIdx.x < n_blocks_a): one item per thread over H*dh/2 q pairs |
-// dh/2 k pairs | dh v elements.  Section B: one wavefront per 128-element chunk
-// of the SwiGLU output, written in block fixed point into the operand of the
-// output projection (chunks H*dh/128 ... of the row).
+// dh/2 k pairs | dh v elements.  Section B: one workgroup per scale block of the
+// SwiGLU output (blk_a chunks of 128, at most 64): each wave takes every fourth
+// chunk, the block maximum fixes one power-of-two scale, and the digits go into
+// the operand of the output projection (chunks H*dh/128 ... of the row).
 // `part` is in packed column order: q|k|v in place, then 64-column groups of
 // (32 gate, 32 up).  Cache element offsets follow the library block layouts.
 __global__ __launch_bounds__(256) void epi_in_kernel(
-    const float* __restrict__ part, int S, const float* __restrict__ scale,
+    const float* __restrict__ part, SkqPlan pl, const float* __restrict__ scale,
     const float* __restrict__ cs, const int32_t* __restrict__ positions, int B, int H, int dh, int F,
     int L_ctx, int n_blocks_a, float* __restrict__ q, uint16_t* __restrict__ kc,
-    uint16_t* __restrict__ vc, unsigned char* __restrict__ actq, float* __restrict__ acts, int nd) {
+    uint16_t* __restrict__ vc, unsigned char* __restrict__ actq, float* __restrict__ acts,
+    int blk_a, int nd) {
+    __shared__ float red[4];
     const int b = blockIdx.y;
     const int half = dh >> 1;
     const int n_q = H * half, n_k = half, n_v = dh;
@@ -122,25 +132,44 @@ __global__ __launch_bounds__(256) void epi_in_kernel(
 
     if ((int)blockIdx.x >= n_blocks_a) {
         const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-        const int j = ((int)blockIdx.x - n_blocks_a) * 4 + wave;  // chunk of the FFN activation
-        if (j >= (F >> 7)) return;
-        const int f = j * QCHUNK + 2 * lane;                      // f and f + 1 share a 32-group
-        const int pcol = n_qkv + (f >> 5) * 64 + (f & 31);
-        float g0 = 0.f, g1 = 0.f, u0 = 0.f, u1 = 0.f;
-        for (int s = 0; s < S; s++) {  // fixed order
-            const float* p = part + (size_t)s * stride + rowoff + pcol;
-            const f32x2 gv = *reinterpret_cast<const f32x2*>(p);
-            const f32x2 uv = *reinterpret_cast<const f32x2*>(p + 32);
-            g0 += gv.x; g1 += gv.y; u0 += uv.x; u1 += uv.y;
+        const int c_lo = ((int)blockIdx.x - n_blocks_a) * blk_a;
+        const int c_hi = c_lo + blk_a < (F >> 7) ? c_lo + blk_a : (F >> 7);
+        float a0[16], a1[16], mx = 0.f;
+#pragma unroll
+        for (int k = 0; k < 16; k++) {
+            const int j = c_lo + wave + 4 * k;  // chunk of the FFN activation
+            a0[k] = a1[k] = 0.f;
+            if (j < c_hi) {
+                const int f = j * QCHUNK + 2 * lane;  // f and f + 1 share a 32-group
+                const int pcol = n_qkv + (f >> 5) * 64 + (f & 31);
+                const int ns = skq_slots(pcol / pl.tile_cols, pl.C, pl.T, pl.G);
+                float g0 = 0.f, g1 = 0.f, u0 = 0.f, u1 = 0.f;
+                for (int s = 0; s < ns; s++) {  // fixed order
+                    const float* p = part + (size_t)s * stride + rowoff + pcol;
+                    const f32x2 gv = *reinterpret_cast<const f32x2*>(p);
+                    const f32x2 uv = *reinterpret_cast<const f32x2*>(p + 32);
+                    g0 += gv.x; g1 += gv.y; u0 += uv.x; u1 += uv.y;
+                }
+                g0 *= scale[pcol]; g1 *= scale[pcol + 1];
+                u0 *= scale[pcol + 32]; u1 *= scale[pcol + 33];
+                // swish(g) = g / (1 + e^-g) = g / (1 + 2^(-g log2 e))
+                a0[k] = g0 / (1.0f + __builtin_amdgcn_exp2f(-g0 * 1.4426950408889634f)) * u0;
+                a1[k] = g1 / (1.0f + __builtin_amdgcn_exp2f(-g1 * 1.4426950408889634f)) * u1;
+                mx = fmaxf(mx, fmaxf(fabsf(a0[k]), fabsf(a1[k])));
+            }
         }
-        g0 *= scale[pcol]; g1 *= scale[pcol + 1];
-        u0 *= scale[pcol + 32]; u1 *= scale[pcol + 33];
-        // swish(g) = g / (1 + e^-g) = g / (1 + 2^(-g log2 e))
-        const float a0 = g0 / (1.0f + __builtin_amdgcn_exp2f(-g0 * 1.4426950408889634f)) * u0;
-        const float a1 = g1 / (1.0f + __builtin_amdgcn_exp2f(-g1 * 1.4426950408889634f)) * u1;
-        const int chunk = (H * dh >> 7) + j;
-        quantize_chunk_wave(a0, a1, lane, nd, actq + ((size_t)b * k_out + (size_t)chunk * QCHUNK) * nd,
-                            acts + (size_t)chunk * QSCALE_ROWS + b);
+        const float s = qscale_from_max(block_max_256(mx, red), nd);
+        const float inv = 1.0f / s;
+#pragma unroll
+        for (int k = 0; k < 16; k++) {
+            const int j = c_lo + wave + 4 * k;
+            if (j < c_hi) {
+                const int chunk = (H * dh >> 7) + j;
+                quantize_pair_store(a0[k], a1[k], inv, nd, lane,
+                                    actq + ((size_t)b * k_out + (size_t)chunk * QCHUNK) * nd);
+                if (lane == 0) acts[(size_t)chunk * QSCALE_ROWS + b] = s;
+            }
+        }
         return;
     }
 
@@ -153,8 +182,8 @@ __global__ __launch_bounds__(256) void epi_in_kernel(
         const int pi = is_k ? item - n_q : item;
         const int head = is_k ? 0 : pi / half, i = pi % half;
         const int col = (is_k ? H * dh : head * dh) + i;
-        float lo = scale[col] * sum_partials(part, S, stride, rowoff + col);
-        float hi = scale[col + half] * sum_partials(part, S, stride, rowoff + col + half);
+        float lo = scale[col] * sum_partials(part, pl, stride, rowoff + col, col);
+        float hi = scale[col + half] * sum_partials(part, pl, stride, rowoff + col + half, col + half);
         const float cn = cs[((size_t)b * half + i) * 2], sn = cs[((size_t)b * half + i) * 2 + 1];
         const float rlo = lo * cn - hi * sn, rhi = hi * cn + lo * sn;
         if (!is_k) {
@@ -172,7 +201,7 @@ __global__ __launch_bounds__(256) void epi_in_kernel(
     } else if (item < n_q + n_k + n_v) {
         const int c = item - n_q - n_k;
         const int col = H * dh + dh + c;
-        float v = scale[col] * sum_partials(part, S, stride, rowoff + col);
+        float v = scale[col] * sum_partials(part, pl, stride, rowoff + col, col);
         if (ok) {
             const size_t blk = ((size_t)b * (L_ctx >> 5) + (P >> 5)) * 32 * dh;
             const int tt = P & 31;
@@ -182,8 +211,8 @@ __global__ __launch_bounds__(256) void epi_in_kernel(
     }
 }
 
-// x' = [x +] scale * sum_s part[s]   (elementwise; partials summed in index order)
-__global__ __launch_bounds__(256) void residual_kernel(const float* __restrict__ part, int S,
+// x' = [x +] scale * sum over slots of part   (elementwise; slots summed in index order)
+__global__ __launch_bounds__(256) void residual_kernel(const float* __restrict__ part, SkqPlan pl,
                                                        const float* __restrict__ scale,
                                                        float* __restrict__ xres, int B, int d,
                                                        int add_residual,
@@ -192,8 +221,9 @@ __global__ __launch_bounds__(256) void residual_kernel(const float* __restrict__
     const int b = blockIdx.y, c = (blockIdx.x * 256 + threadIdx.x) * 4;
     if (c >= d) return;
     const size_t stride = (size_t)B * d, off = (size_t)b * d + c;
+    const int ns = skq_slots(c / pl.tile_cols, pl.C, pl.T, pl.G);  // 4 columns share a tile
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-    for (int s = 0; s < S; s++) acc += *reinterpret_cast<const f32x4*>(part + (size_t)s * stride + off);
+    for (int s = 0; s < ns; s++) acc += *reinterpret_cast<const f32x4*>(part + (size_t)s * stride + off);
     const f32x4 sc = *reinterpret_cast<const f32x4*>(scale + c);
     f32x4 xn = sc * acc;
     if (add_residual) xn += *reinterpret_cast<const f32x4*>(xres + off);
@@ -225,25 +255,26 @@ hipError_t launch_ln(const float* xres, const float* gamma, int B, int d, float 
     return hipGetLastError();
 }
 
-hipError_t launch_epi_in(const float* part, int S, const float* scale, const float* cs,
+hipError_t launch_epi_in(const float* part, SkqPlan pl, const float* scale, const float* cs,
                          const int32_t* positions, int B, int H, int dh, int F, int L_ctx,
                          float* q, void* kc_layer, void* vc_layer, void* actq, float* acts,
-                         int nd, hipStream_t stream) {
+                         int blk_a, int nd, hipStream_t stream) {
+    if (blk_a < 1 || blk_a > 64) return hipErrorInvalidValue;
     const int items = H * dh / 2 + dh / 2 + dh;
     const int n_blocks_a = (items + 255) / 256;
-    const int n_blocks_b = (F / 128 + 3) / 4;
+    const int n_blocks_b = (F / 128 + blk_a - 1) / blk_a;
     epi_in_kernel<<<dim3(n_blocks_a + n_blocks_b, B), dim3(256), 0, stream>>>(
-        part, S, scale, cs, positions, B, H, dh, F, L_ctx, n_blocks_a, q,
+        part, pl, scale, cs, positions, B, H, dh, F, L_ctx, n_blocks_a, q,
         reinterpret_cast<uint16_t*>(kc_layer), reinterpret_cast<uint16_t*>(vc_layer),
-        reinterpret_cast<unsigned char*>(actq), acts, nd);
+        reinterpret_cast<unsigned char*>(actq), acts, blk_a, nd);
     return hipGetLastError();
 }
 
-hipError_t launch_residual(const float* part, int S, const float* scale, float* xres, int B, int d,
-                           int add_residual, uint16_t* x_out_bf16, float* y_out_f32,
+hipError_t launch_residual(const float* part, SkqPlan pl, const float* scale, float* xres, int B,
+                           int d, int add_residual, uint16_t* x_out_bf16, float* y_out_f32,
                            hipStream_t stream) {
     residual_kernel<<<dim3((d / 4 + 255) / 256, B), dim3(256), 0, stream>>>(
-        part, S, scale, xres, B, d, add_residual, x_out_bf16, y_out_f32);
+        part, pl, scale, xres, B, d, add_residual, x_out_bf16, y_out_f32);
     return hipGetLastError();
 }
 

@@ -2,197 +2,337 @@
 // with one scale per output channel; Section 3.4: the fused input and output
 // projections of the parallel block are the two instances of this product).
 //
-//   part[s][b][n] = sum_{k in split s} a[b][k] * q8[k][n]          (fp32, unscaled)
+//   part[slot][b][n] = sum_{k in a K-range} a[b][k] * q8[k][n]        (fp32, unscaled)
 //
 // The per-channel weight scale s[n] is applied once per output by the consumer
 // of the partial sums, which is exact because it does not depend on k.
 //
-// Activations arrive in block fixed point (common.h): ND int8 digit planes and
-// a power-of-two scale per (row, 128-k chunk).  Every digit goes through
-// v_mfma_i32_32x32x32_i8 against the raw int8 weights -- no weight conversion,
-// exact int32 sums -- and once per chunk the int32 tiles are folded into the
-// fp32 accumulator:  acc += scale[b][chunk] * (65536 * float(top) + float((mid << 8) + low)).
-// ND = 3 gives 23-bit activations (the bf16 rounding of LayerNorm and SwiGLU
+// Arithmetic.  Activations arrive in block fixed point (common.h): ND int8 digit
+// planes and a power-of-two scale per (row, 128-k chunk).  Every digit plane goes
+// through v_mfma_i32_32x32x32_i8 against the raw int8 weights -- no weight
+// conversion, exact int32 sums, one int32 accumulator per plane -- and every
+// `fold_chunks` chunks (over which the producer keeps the scale constant) the
+// planes are folded into the fp32 accumulator:
+//     acc += scale[b] * (65536 * float(top) + 256 * float(mid) + float(low)).
+// ND = 3 gives 23-bit activations (bf16 rounding of the LayerNorm and SwiGLU
 // outputs would otherwise dominate the error of a deep stack) for 1.5x the MFMA
-// time of a single bf16 pass; ND = 2 gives 15 bits for 1.0x.
+// time of a single bf16 pass.
 //
-// Data movement (HBM-bound: 1 byte per weight, 2*B flops per byte):
+// Data movement (HBM-bound: 1 byte per weight, 2*B flops per byte).
 //   - weights are pre-tiled by pd_pack_* so that a wavefront's 16-byte-per-lane
 //     load is 1 KiB contiguous and is already an MFMA B operand:
 //     packed[(st*(K/32) + kb)*64 + lane] holds W[kb*32 + (lane/32)*16 + 0..15][st*32 + lane%32];
+//     each wave keeps PF units of its weight stream in flight in registers;
 //   - activations (and their scales) are shared by the 4 waves through LDS.
 // A = activations (M = batch row), B = weights (N = output channel).
+//
+// Work split (deterministic stream-K).  The matrix is cut into units = (tile of
+// 128*NS columns, 128-k chunk), ordered tile-major; workgroup g of G takes the
+// contiguous range [g*U/G, (g+1)*U/G).  All workgroups stream the same number of
+// bytes (+-1 unit), whatever the matrix shape.  A tile covered by several
+// workgroups gets one partial per workgroup, in slot (g - first g of the tile);
+// consumers add the slots in index order, so results do not depend on timing.
 #include "common.h"
 #include "kernels.h"
 
 namespace pd {
 
-// BM: 32-row batch blocks held in accumulators; NS: 32-column subtiles per wave.
-// Workgroup = 4 waves = 128*NS columns x one K-split x one group of 32*BM rows.
-// grid = (n_tiles, S, row groups).
-template <int BM, int NS, int ND>
-__global__ __launch_bounds__(256) void qgemm_kernel(const uint4* __restrict__ wp,
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also drains
+// every outstanding global load (vmcnt(0)), which would serialise the weight
+// prefetch with each unit; here only the LDS counter is waited on.
+__device__ __forceinline__ void lds_barrier() {
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+// BM: 32-row batch blocks held in accumulators; NS: 32-column subtiles per wave;
+// R: weight units per wave held in a register ring (R - 1 in flight while one is
+// consumed).  grid = (G workgroups, row groups of 32*BM rows).
+//
+// Weights go HBM -> registers with non-temporal 16-byte loads (each is 1 KiB
+// contiguous per wave and already a B operand); the loop body is unrolled R
+// times so every ring slot is a fixed register range and the compiler's own
+// vmcnt bookkeeping keeps exactly R - 1 units in flight.  Every step issues the
+// same loads unconditionally (past the end of the range the last unit is
+// fetched again, an L2 hit) so that no control-flow join weakens those waits.
+// Activations of the next unit travel L2 -> registers -> LDS behind the MFMAs
+// of the current one and are shared by the 4 waves.
+constexpr int NT = 512;  // threads per GEMM workgroup (8 waves, two per SIMD)
+
+template <int BM, int NS, int ND, int R>
+__global__ __launch_bounds__(NT) void qgemm_kernel(const uint4* __restrict__ wp,
                                                     const unsigned char* __restrict__ qa,
                                                     const float* __restrict__ scale_t,
                                                     float* __restrict__ part, int B, int K, int N,
-                                                    int S) {
-    constexpr int KC = QCHUNK;                  // k-extent of one LDS stage = one scale block
+                                                    int c_split, int blk0, int blk1) {
+    constexpr int KC = QCHUNK;                  // k-extent of one unit = one LDS stage
     constexpr int ROWS = BM * 32;
     constexpr int PITCH = ND * KC + 16;         // bytes; +16 spreads rows over LDS banks
     constexpr int PPR = ND * KC / 16;           // 16-byte pieces per row per stage
-    constexpr int APT = ROWS * PPR / 256;       // pieces per thread per stage
-    static_assert(ROWS * PPR % 256 == 0, "stage must split evenly over 256 threads");
-    constexpr int KB = KC / 32;                 // 32-k blocks per stage
+    constexpr int APT = (ROWS * PPR + NT - 1) / NT;  // pieces per thread per stage (tail repeats the last piece)
+    constexpr int KB = KC / 32;                 // 32-k blocks per unit
+    constexpr int TSUB = (NT / 64) * NS;        // 32-column subtiles per tile
     constexpr int STAGE = ROWS * PITCH + ROWS * 4;  // digits + one scale per row
+    static_assert(R == 2 || R == 4 || R == 6, "ring depth (even: the activation register stages alternate)");
     __shared__ __attribute__((aligned(16))) unsigned char lds[2][STAGE];
+    // fp32 tile accumulator, one private column per thread: it is touched only when
+    // a scale block or a tile ends, so it lives in LDS and leaves the registers to
+    // the int32 accumulators and the weight ring
+    __shared__ float accl[NS * BM * 16][NT];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int g = lane >> 5, l32 = lane & 31;
-    const int n_sub = N >> 5;                   // 32-column subtiles in the matrix
+    const int n_sub = N >> 5;
     const int kblocks = K >> 5;
-    const int chunks = K >> 7;
-    const int s = blockIdx.y;
-    const int row0 = blockIdx.z * ROWS;         // first batch row of this group
-    const int c_begin = (int)(((long long)s * chunks) / S);
-    const int c_end = (int)(((long long)(s + 1) * chunks) / S);
-    const size_t row_pitch = (size_t)K * ND;    // bytes per activation row
+    const int C = K >> 7;                                   // chunks per tile
+    const int T = (n_sub + TSUB - 1) / TSUB;                // tiles
+    const long long U = (long long)T * C;
+    const int G = gridDim.x;
+    const long long u0 = (long long)blockIdx.x * U / G, u1 = ((long long)blockIdx.x + 1) * U / G;
+    if (u0 >= u1) return;
+    const int row0 = blockIdx.y * ROWS;
 
-    int st[NS];
-    bool st_ok[NS];
-    const uint4* wptr[NS];
+    // byte offsets (within one chunk column of the activation matrix) of the pieces
+    // this thread moves; rows >= B repeat row B-1 (their results are never stored)
+    uint32_t aoff[APT], aslot[APT];
 #pragma unroll
-    for (int i = 0; i < NS; i++) {
-        st[i] = (blockIdx.x * 4 + wave) * NS + i;
-        st_ok[i] = st[i] < n_sub;
-        int stc = st_ok[i] ? st[i] : n_sub - 1;  // clamp: loads stay in bounds, result dropped
-        wptr[i] = wp + ((size_t)stc * kblocks + (size_t)c_begin * KB) * 64 + lane;
+    for (int it = 0; it < APT; it++) {
+        int p_ = it * NT + tid;
+        p_ = p_ < ROWS * PPR ? p_ : ROWS * PPR - 1;
+        aslot[it] = (p_ / PPR) * PITCH + (p_ % PPR) * 16;
+        int rg = row0 + p_ / PPR;
+        rg = rg < B ? rg : B - 1;
+        aoff[it] = (uint32_t)rg * (uint32_t)(K * ND) + (p_ % PPR) * 16;
     }
+    int srow = row0 + tid;
+    srow = srow < B ? srow : B - 1;
 
-    f32x16 acc[NS][BM];
-    i32x16 iacc[NS][BM];
+    i32x16 iacc[ND][NS][BM];
 #pragma unroll
     for (int i = 0; i < NS; i++)
 #pragma unroll
-        for (int bm = 0; bm < BM; bm++)
+        for (int bm = 0; bm < BM; bm++) {
 #pragma unroll
-            for (int r = 0; r < 16; r++) {
-                acc[i][bm][r] = 0.f;
-                iacc[i][bm][r] = 0;
-            }
+            for (int r = 0; r < 16; r++) accl[(i * BM + bm) * 16 + r][tid] = 0.f;
+#pragma unroll
+            for (int p = 0; p < ND; p++)
+#pragma unroll
+                for (int r = 0; r < 16; r++) iacc[p][i][bm][r] = 0;
+        }
 
-    uint4 wcur[NS][KB], wnext[NS][KB], areg[APT];
-    float sreg = 0.f;
+    uint4 wreg[R][NS][KB];
+    const uint4* wsrc[NS];
+    u32x4 areg[2][APT];
+    float sreg[2] = {0.f, 0.f};
 
-#define PD_LOAD_W(dst, c)                                                                \
-    _Pragma("unroll") for (int i = 0; i < NS; i++)                                       \
-        _Pragma("unroll") for (int kb = 0; kb < KB; kb++)                                \
-            dst[i][kb] = ld_stream(wptr[i] + ((size_t)((c) - c_begin) * KB + kb) * 64)
-#define PD_LOAD_A(c)                                                                     \
-    _Pragma("unroll") for (int it = 0; it < APT; it++) {                                 \
-        const int p_ = it * 256 + tid;                                                   \
-        int row_ = row0 + p_ / PPR;                                                      \
-        row_ = row_ < B ? row_ : B - 1; /* rows >= B: duplicate, never stored */         \
-        areg[it] = *reinterpret_cast<const uint4*>(qa + (size_t)row_ * row_pitch +       \
-                                                   (size_t)(c) * (ND * KC) + (p_ % PPR) * 16); \
-    }                                                                                    \
-    if (tid < ROWS) {                                                                    \
-        int row_ = row0 + tid;                                                           \
-        row_ = row_ < B ? row_ : B - 1;                                                  \
-        sreg = scale_t[(size_t)(c) * QSCALE_ROWS + row_];                                \
+    // (tile, chunk) of the unit being computed; of the next weight unit to fetch
+    // (saturates at the last unit of the range); chunk of the next activation stage
+    int t_cur = (int)(u0 / C), c_cur = (int)(u0 % C);
+    int t_w = t_cur, c_w = c_cur, c_a = c_cur;
+    long long u = u0, u_w = u0, u_a = u0;
+
+    // end of the scale block that holds chunk c: chunks [0, c_split) come in blocks
+    // of blk0, chunks [c_split, C) in blocks of blk1
+    auto block_end = [&](int c) {
+        int e;
+        if (c < c_split) {
+            e = (c / blk0 + 1) * blk0;
+            e = e < c_split ? e : c_split;
+        } else {
+            e = c_split + ((c - c_split) / blk1 + 1) * blk1;
+            e = e < C ? e : C;
+        }
+        return e;
+    };
+    int seg_end = block_end(c_cur);
+
+    // weight unit (t_w, c_w) -> ring slot s, one 32-k block at a time
+#define PD_W_PTRS()                                                                      \
+    _Pragma("unroll") for (int i = 0; i < NS; i++) {                                     \
+        int st_ = t_w * TSUB + wave * NS + i;                                            \
+        st_ = st_ < n_sub ? st_ : n_sub - 1; /* ragged last tile: result dropped */      \
+        wsrc[i] = wp + ((size_t)st_ * kblocks + (size_t)c_w * KB) * 64 + lane;           \
     }
-#define PD_STORE_A(buf)                                                                  \
-    _Pragma("unroll") for (int it = 0; it < APT; it++) {                                 \
-        const int p_ = it * 256 + tid;                                                   \
-        *reinterpret_cast<uint4*>(&lds[buf][(p_ / PPR) * PITCH + (p_ % PPR) * 16]) = areg[it]; \
-    }                                                                                    \
-    if (tid < ROWS) *reinterpret_cast<float*>(&lds[buf][ROWS * PITCH + tid * 4]) = sreg;
-    // plane 0 of a row chunk is the most significant digit
-#define PD_MFMA_PLANE(buf, plane)                                                        \
-    _Pragma("unroll") for (int kb = 0; kb < KB; kb++) {                                  \
-        i32x4 aop[BM];                                                                   \
-        _Pragma("unroll") for (int bm = 0; bm < BM; bm++)                                \
-            aop[bm] = *reinterpret_cast<const i32x4*>(                                   \
-                &lds[buf][(bm * 32 + l32) * PITCH + (plane) * KC + kb * 32 + g * 16]);   \
-        _Pragma("unroll") for (int i = 0; i < NS; i++) {                                 \
-            const i32x4 bop = __builtin_bit_cast(i32x4, wcur[i][kb]);                    \
-            _Pragma("unroll") for (int bm = 0; bm < BM; bm++)                            \
-                iacc[i][bm] = __builtin_amdgcn_mfma_i32_32x32x32_i8(aop[bm], bop,        \
-                                                                    iacc[i][bm], 0, 0, 0); \
+#define PD_W_LOAD(s, kb)                                                                 \
+    _Pragma("unroll") for (int i = 0; i < NS; i++) wreg[s][i][kb] = ld_stream(wsrc[i] + (kb) * 64);
+#define PD_W_NEXT()                                                                      \
+    if (u_w + 1 < u1) {                                                                  \
+        u_w++;                                                                           \
+        if (++c_w == C) { c_w = 0; t_w++; }                                              \
+    }
+#define PD_FETCH_W(s)                                                                    \
+    {                                                                                    \
+        PD_W_PTRS()                                                                      \
+        _Pragma("unroll") for (int kb = 0; kb < KB; kb++) { PD_W_LOAD(s, kb) }           \
+        PD_W_NEXT()                                                                      \
+    }
+    // activations of the unit two steps ahead -> register stage `as`; vector-memory
+    // operations retire in order, so a load that is waited on must be older than
+    // everything that is meant to stay in flight: these loads are consumed one step
+    // after they are issued, with R - 1 weight units still outstanding behind them
+#define PD_LOAD_A(as)                                                                    \
+    {                                                                                    \
+        if (u_a + 1 < u1) {                                                              \
+            u_a++;                                                                       \
+            if (++c_a == C) c_a = 0;                                                     \
         }                                                                                \
+        const unsigned char* base_ = qa + (size_t)c_a * (ND * KC);                       \
+        _Pragma("unroll") for (int it = 0; it < APT; it++)                               \
+            areg[as][it] = *reinterpret_cast<const u32x4*>(base_ + aoff[it]);            \
+        if (tid < ROWS) sreg[as] = scale_t[(size_t)c_a * QSCALE_ROWS + srow];            \
     }
-    // acc += (scale * mult) * float(iacc); iacc = 0.  Rows 8*q + 4*g + 0..3 of a
-    // block: one float4 of scales per q.
-#define PD_FOLD(buf, mult)                                                               \
+#define PD_STORE_A(buf, as)                                                              \
+    {                                                                                    \
+        _Pragma("unroll") for (int it = 0; it < APT; it++)                               \
+            *reinterpret_cast<u32x4*>(&lds[buf][aslot[it]]) = areg[as][it];              \
+        if (tid < ROWS) *reinterpret_cast<float*>(&lds[buf][ROWS * PITCH + tid * 4]) = sreg[as]; \
+    }
+    // One unit of MFMAs.  Group gi = (kb, plane p): BM operand reads from LDS feed
+    // NS*BM MFMAs; the reads run two groups ahead of the MFMAs, and scheduling
+    // barriers keep that order (left alone, the scheduler hoists every read of the
+    // unit and runs out of registers).  As soon as the last plane of a 32-k block
+    // is issued, the ring registers of that block are refilled from the next unit.
+    // Plane 0 of a row chunk is the most significant digit.
+#define PD_A_READ(buf, gi, slot)                                                         \
+    _Pragma("unroll") for (int bm = 0; bm < BM; bm++)                                    \
+        aop[slot][bm] = *reinterpret_cast<const i32x4*>(                                 \
+            &lds[buf][(bm * 32 + l32) * PITCH + ((gi) % ND) * KC + ((gi) / ND) * 32 + g * 16]);
+#define PD_MFMA(buf, s)                                                                  \
+    {                                                                                    \
+        i32x4 aop[3][BM];                                                                \
+        PD_W_PTRS()                                                                      \
+        PD_A_READ(buf, 0, 0)                                                             \
+        PD_A_READ(buf, 1, 1)                                                             \
+        _Pragma("unroll") for (int gi = 0; gi < KB * ND; gi++) {                         \
+            if (gi + 2 < KB * ND) { PD_A_READ(buf, gi + 2, (gi + 2) % 3) }               \
+            _Pragma("unroll") for (int i = 0; i < NS; i++)                               \
+                _Pragma("unroll") for (int bm = 0; bm < BM; bm++)                        \
+                    iacc[gi % ND][i][bm] = __builtin_amdgcn_mfma_i32_32x32x32_i8(        \
+                        aop[gi % 3][bm], __builtin_bit_cast(i32x4, wreg[s][i][gi / ND]), \
+                        iacc[gi % ND][i][bm], 0, 0, 0);                                  \
+            if (gi % ND == ND - 1) { PD_W_LOAD(s, gi / ND) }                             \
+            __builtin_amdgcn_sched_barrier(0);                                           \
+        }                                                                                \
+        PD_W_NEXT()                                                                      \
+    }
+    // acc += scale * sum_p 256^(ND-1-p) * float(iacc[p]); iacc = 0.  int32 bound per
+    // plane and scale block: 128 * 127 * 128 * chunks < 2^31 for blocks of up to 1023
+    // chunks.  Lane (l32, g) holds rows 8q + 4g + 0..3 of each 32-row block.
+#define PD_FOLD(buf)                                                                     \
     _Pragma("unroll") for (int bm = 0; bm < BM; bm++) {                                  \
         f32x4 sc[4];                                                                     \
         _Pragma("unroll") for (int q = 0; q < 4; q++)                                    \
             sc[q] = *reinterpret_cast<const f32x4*>(                                     \
-                        &lds[buf][ROWS * PITCH + (bm * 32 + 8 * q + 4 * g) * 4]) * (mult); \
-        _Pragma("unroll") for (int i = 0; i < NS; i++)                                   \
+                &lds[buf][ROWS * PITCH + (bm * 32 + 8 * q + 4 * g) * 4]);                \
+        _Pragma("unroll") for (int i = 0; i < NS; i++) {                                 \
             _Pragma("unroll") for (int r = 0; r < 16; r++) {                             \
-                acc[i][bm][r] += sc[r >> 2][r & 3] * (float)iacc[i][bm][r];              \
-                iacc[i][bm][r] = 0;                                                      \
+                float v_ = (float)iacc[0][i][bm][r];                                     \
+                _Pragma("unroll") for (int p = 1; p < ND; p++)                           \
+                    v_ = v_ * 256.0f + (float)iacc[p][i][bm][r];                         \
+                accl[(i * BM + bm) * 16 + r][tid] += sc[r >> 2][r & 3] * v_;             \
+                _Pragma("unroll") for (int p = 0; p < ND; p++) iacc[p][i][bm][r] = 0;    \
             }                                                                            \
+            __builtin_amdgcn_sched_barrier(0); /* one tile at a time: bounded live set */ \
+        }                                                                                \
     }
-#define PD_SHIFT8()                                                                      \
-    _Pragma("unroll") for (int i = 0; i < NS; i++)                                       \
-        _Pragma("unroll") for (int bm = 0; bm < BM; bm++)                                \
-            _Pragma("unroll") for (int r = 0; r < 16; r++) iacc[i][bm][r] <<= 8;
-    // int32 bounds per 128-k chunk: one plane 127*128*128 < 2^21; two planes
-    // combined 32640*127*128 < 2^29.  Three planes would overflow, so the top
-    // digit of ND = 3 is folded on its own.
-#define PD_COMPUTE(buf)                                                                  \
-    if (ND == 3) {                                                                       \
-        PD_MFMA_PLANE(buf, 0)                                                            \
-        PD_FOLD(buf, 65536.0f)                                                           \
-    }                                                                                    \
-    PD_MFMA_PLANE(buf, ND - 2)                                                           \
-    PD_SHIFT8()                                                                          \
-    PD_MFMA_PLANE(buf, ND - 1)                                                           \
-    PD_FOLD(buf, 1.0f)
+    // D layout of the 32x32 MFMA: register r of lane (l32, g) is row 8*(r/4) + 4*g + r%4, column l32
+#define PD_STORE_TILE()                                                                  \
+    {                                                                                    \
+        const int slot_ = (int)blockIdx.x - skq_owner((long long)t_cur * C, U, G);       \
+        _Pragma("unroll") for (int i = 0; i < NS; i++) {                                 \
+            const int st_ = t_cur * TSUB + wave * NS + i;                                \
+            if (st_ < n_sub) {                                                           \
+                const int n_ = st_ * 32 + l32;                                           \
+                _Pragma("unroll") for (int bm = 0; bm < BM; bm++) {                      \
+                    _Pragma("unroll") for (int r = 0; r < 16; r++) {                     \
+                        const int b_ = row0 + bm * 32 + 8 * (r >> 2) + 4 * g + (r & 3);  \
+                        if (b_ < B)                                                      \
+                            part[((size_t)slot_ * B + b_) * N + n_] = accl[(i * BM + bm) * 16 + r][tid]; \
+                    }                                                                    \
+                    __builtin_amdgcn_sched_barrier(0);                                   \
+                }                                                                        \
+            }                                                                            \
+            _Pragma("unroll") for (int bm = 0; bm < BM; bm++)                            \
+                _Pragma("unroll") for (int r = 0; r < 16; r++)                           \
+                    accl[(i * BM + bm) * 16 + r][tid] = 0.f;                             \
+        }                                                                                \
+    }
+    // One unit: fetch the next activation stage into registers, multiply the current
+    // one, refill the ring slot just consumed, close a scale block / tile if this
+    // unit ended one (the scales are read before the barrier: afterwards another
+    // wave may already overwrite this stage), publish the next stage.
+#define PD_STEP(s)                                                                       \
+    {                                                                                    \
+        PD_LOAD_A((s) % 2)                                                               \
+        __builtin_amdgcn_sched_barrier(0);                                               \
+        PD_MFMA(cur, s)                                                                  \
+        c_cur++;                                                                         \
+        u++;                                                                             \
+        if (c_cur == seg_end || u == u1) {                                               \
+            PD_FOLD(cur)                                                                 \
+            if (c_cur == C || u == u1) {                                                 \
+                PD_STORE_TILE()                                                          \
+                if (c_cur == C) { c_cur = 0; t_cur++; }                                  \
+            }                                                                            \
+            seg_end = block_end(c_cur);                                                  \
+        }                                                                                \
+        __builtin_amdgcn_sched_barrier(0);                                               \
+        PD_STORE_A(cur ^ 1, ((s) + 1) % 2)                                               \
+        lds_barrier();                                                                   \
+        cur ^= 1;                                                                        \
+    }
 
-    if (c_begin < c_end) {
-        PD_LOAD_W(wcur, c_begin);
-        PD_LOAD_A(c_begin);
-        PD_STORE_A(0);
-        __syncthreads();
-        int cur = 0;
-        // steady state: fetch chunk c + 1 while the MFMAs consume chunk c
-        for (int c = c_begin; c + 1 < c_end; c++) {
-            PD_LOAD_W(wnext, c + 1);
-            PD_LOAD_A(c + 1);
-            PD_COMPUTE(cur);
-            PD_STORE_A(cur ^ 1);
-            __syncthreads();
+    // prologue: activations of the first unit straight into stage 0, those of the
+    // second into register stage 1 (where step 0 expects them), R weight units in flight
+    {
+        const unsigned char* base_ = qa + (size_t)c_a * (ND * KC);
 #pragma unroll
-            for (int i = 0; i < NS; i++)
-#pragma unroll
-                for (int kb = 0; kb < KB; kb++) wcur[i][kb] = wnext[i][kb];
-            cur ^= 1;
-        }
-        PD_COMPUTE(cur);  // last chunk, nothing left to fetch
+        for (int it = 0; it < APT; it++) areg[0][it] = *reinterpret_cast<const u32x4*>(base_ + aoff[it]);
+        if (tid < ROWS) sreg[0] = scale_t[(size_t)c_a * QSCALE_ROWS + srow];
     }
-#undef PD_LOAD_W
+    PD_STORE_A(0, 0)
+    PD_LOAD_A(1)
+    PD_FETCH_W(0)
+    PD_FETCH_W(1)
+    if constexpr (R > 2) { PD_FETCH_W(2) }
+    if constexpr (R > 3) { PD_FETCH_W(3) }
+    if constexpr (R > 4) { PD_FETCH_W(4) }
+    if constexpr (R > 5) { PD_FETCH_W(5) }
+    lds_barrier();
+
+    int cur = 0;
+    for (;;) {
+        PD_STEP(0)
+        if (u == u1) break;
+        PD_STEP(1)
+        if (u == u1) break;
+        if constexpr (R > 2) {
+            PD_STEP(2)
+            if (u == u1) break;
+        }
+        if constexpr (R > 3) {
+            PD_STEP(3)
+            if (u == u1) break;
+        }
+        if constexpr (R > 4) {
+            PD_STEP(4)
+            if (u == u1) break;
+        }
+        if constexpr (R > 5) {
+            PD_STEP(5)
+            if (u == u1) break;
+        }
+    }
+#undef PD_FETCH_W
+#undef PD_W_PTRS
+#undef PD_W_LOAD
+#undef PD_W_NEXT
+#undef PD_A_READ
 #undef PD_LOAD_A
 #undef PD_STORE_A
-#undef PD_MFMA_PLANE
+#undef PD_MFMA
 #undef PD_FOLD
-#undef PD_SHIFT8
-#undef PD_COMPUTE
-
-    // D layout of the 32x32 MFMA: register r of lane (l32, g) is row 8*(r/4) + 4*g + r%4, column l32
-#pragma unroll
-    for (int i = 0; i < NS; i++) {
-        if (!st_ok[i]) continue;
-        const int n = st[i] * 32 + l32;
-#pragma unroll
-        for (int bm = 0; bm < BM; bm++)
-#pragma unroll
-            for (int r = 0; r < 16; r++) {
-                int b = row0 + bm * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
-                if (b < B) part[((size_t)s * B + b) * N + n] = acc[i][bm][r];
-            }
-    }
+#undef PD_STORE_TILE
+#undef PD_STEP
 }
 
 // bf16 [B][K] -> block fixed point (test entry pd_qgemm): one wave per (row, chunk)
@@ -249,15 +389,16 @@ __global__ __launch_bounds__(256) void pack_vector_kernel(const uint16_t* __rest
     if (pn < N) dst[pn] = from_bf16(src[col_map(pn, mode, n_qkv, F)]);
 }
 
-// out[b][n] = scale[n] * sum_s part[s][b][n]   (fixed summation order)
+// out[b][n] = scale[n] * sum over the slots of n's tile (fixed order)
 __global__ __launch_bounds__(256) void qgemm_reduce_kernel(const float* __restrict__ part,
                                                            const float* __restrict__ scale,
                                                            float* __restrict__ out, int B, int N,
-                                                           int S) {
+                                                           SkqPlan pl) {
     int n = blockIdx.x * 256 + threadIdx.x, b = blockIdx.y;
     if (n >= N) return;
+    const int ns = skq_slots(n / pl.tile_cols, pl.C, pl.T, pl.G);
     float acc = 0.f;
-    for (int s = 0; s < S; s++) acc += part[((size_t)s * B + b) * N + n];
+    for (int s = 0; s < ns; s++) acc += part[((size_t)s * B + b) * N + n];
     out[(size_t)b * N + n] = scale[n] * acc;
 }
 
@@ -265,41 +406,58 @@ __global__ __launch_bounds__(256) void qgemm_reduce_kernel(const float* __restri
 
 void qgemm_config(int B, int* bm, int* ns, int* tile_cols) {
     int blocks = (B + 31) / 32;
-    int BMv = blocks <= 1 ? 1 : blocks <= 2 ? 2 : 4;  // more than 128 rows: several row groups
-    *bm = BMv;
-    *ns = BMv <= 2 ? 2 : 1;
-    *tile_cols = 128 * *ns;
+    *bm = blocks <= 1 ? 1 : 2;  // more than 64 rows: several row groups
+    *ns = 1;
+    *tile_cols = (NT / 64) * 32 * *ns;
 }
 
-int qgemm_auto_splits(int B, int K, int N) {
+SkqPlan qgemm_skq(int B, int K, int N, int G) {
     int bm, ns, tc;
     qgemm_config(B, &bm, &ns, &tc);
-    int n_tiles = (N + tc - 1) / tc * ((B + 32 * bm - 1) / (32 * bm));
-    int s = (400 + n_tiles / 2) / n_tiles;
-    int cap = K / 128 < PD_MAX_SPLITS ? K / 128 : PD_MAX_SPLITS;
-    if (s < 1) s = 1;
-    if (s > cap) s = cap;
-    return s;
+    return SkqPlan{tc, K / 128, (N + tc - 1) / tc, G};
+}
+
+// Workgroups per row group and partial slots per tile for a [K][N] projection.
+void qgemm_plan(int B, int K, int N, int num_cus, int* G, int* slots) {
+    int bm, ns, tc;
+    qgemm_config(B, &bm, &ns, &tc);
+    const int T = (N + tc - 1) / tc, C = K / 128;
+    const long long U = (long long)T * C;
+    long long g = num_cus;
+    if (g > U) g = U;
+    // a tile is shared by at most ceil(G / T) + 1 workgroups: keep that within PD_MAX_SPLITS
+    const long long cap = (long long)(PD_MAX_SPLITS - 1) * T;
+    if (g > cap) g = cap;
+    if (g < 1) g = 1;
+    int mx = 1;
+    for (int t = 0; t < T; t++) {
+        int n = skq_owner((long long)(t + 1) * C - 1, U, (int)g) - skq_owner((long long)t * C, U, (int)g) + 1;
+        if (n > mx) mx = n;
+    }
+    *G = (int)g;
+    *slots = mx;
 }
 
 hipError_t launch_qgemm(const void* wp, const void* qa, const float* scale_t, float* part, int B,
-                        int K, int N, int S, int nd, hipStream_t stream) {
+                        int K, int N, int G, int c_split, int blk0, int blk1, int nd,
+                        hipStream_t stream) {
     int bm, ns, tc;
     qgemm_config(B, &bm, &ns, &tc);
-    dim3 grid((N + tc - 1) / tc, S, (B + 32 * bm - 1) / (32 * bm)), block(256);
+    dim3 grid(G, (B + 32 * bm - 1) / (32 * bm)), block(NT);
     const uint4* w4 = reinterpret_cast<const uint4*>(wp);
     const unsigned char* q = reinterpret_cast<const unsigned char*>(qa);
-#define PD_LAUNCH(BMv, NSv)                                                                 \
+#define PD_LAUNCH(BMv, NSv, PD_RING)                                                                 \
     do {                                                                                    \
         if (nd == 3)                                                                        \
-            qgemm_kernel<BMv, NSv, 3><<<grid, block, 0, stream>>>(w4, q, scale_t, part, B, K, N, S); \
+            qgemm_kernel<BMv, NSv, 3, PD_RING><<<grid, block, 0, stream>>>(w4, q, scale_t, part, B, K, N, c_split, blk0, blk1); \
         else                                                                                \
-            qgemm_kernel<BMv, NSv, 2><<<grid, block, 0, stream>>>(w4, q, scale_t, part, B, K, N, S); \
+            qgemm_kernel<BMv, NSv, 2, PD_RING><<<grid, block, 0, stream>>>(w4, q, scale_t, part, B, K, N, c_split, blk0, blk1); \
     } while (0)
     if (nd != 2 && nd != 3) return hipErrorInvalidValue;
-    if (bm == 1) PD_LAUNCH(1, 2);
-    else if (bm == 2) PD_LAUNCH(2, 2);
-    else PD_LAUNCH(4, 1);
+    if (blk0 < 1 || blk0 > 1024 || blk1 < 1 || blk1 > 1024 || c_split < 0 || c_split > K / 128)
+        return hipErrorInvalidValue;
+    if (bm == 1) PD_LAUNCH(1, 1, 6);
+    else PD_LAUNCH(2, 1, 4);
 #undef PD_LAUNCH
     return hipGetLastError();
 }
@@ -325,9 +483,10 @@ hipError_t launch_pack_vector(const uint16_t* src, float* dst, int N, int mode, 
     return hipGetLastError();
 }
 
-hipError_t launch_qgemm_reduce(const float* part, const float* scale, float* out, int B, int N,
-                               int S, hipStream_t stream) {
-    qgemm_reduce_kernel<<<dim3((N + 255) / 256, B), dim3(256), 0, stream>>>(part, scale, out, B, N, S);
+hipError_t launch_qgemm_reduce(const float* part, const float* scale, float* out, int B, int K,
+                               int N, int G, hipStream_t stream) {
+    qgemm_reduce_kernel<<<dim3((N + 255) / 256, B), dim3(256), 0, stream>>>(
+        part, scale, out, B, N, qgemm_skq(B, K, N, G));
     return hipGetLastError();
 }
 

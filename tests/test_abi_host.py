@@ -90,7 +90,8 @@ def test_argument_errors_come_before_any_launch(binding):
     with pytest.raises(binding.PdError):
         dec.set_option("no_such_option", 1)
     with pytest.raises(binding.PdError):
-        dec.set_option("split_in", 3)   # d_model 256 has only two 128-row chunks
-    dec.set_option("split_in", 2)
+        dec.set_option("gemm_workgroups_in", 5000)   # at most 4096
+    dec.set_option("gemm_workgroups_in", 2)
+    dec.set_option("gemm_workgroups_in", 0)
     assert L.pd_status_string(i32(-7)).decode().startswith("position")
     dec.close()
