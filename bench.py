@@ -69,11 +69,14 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="c3_62b")
+    ap.add_argument("--layers", type=int, default=0,
+                    help="run a shorter stack of the same layer shape (kernel tuning; not the headline workload)")
     ap.add_argument("--no-graph", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--gemm-wg-in", type=int, default=0)
     ap.add_argument("--gemm-wg-out", type=int, default=0)
     ap.add_argument("--attn-bps", type=int, default=0)
+    ap.add_argument("--act-digits", type=int, default=0)
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus must be 1",
@@ -86,10 +89,12 @@ def main():
     from paper_2211_05102_amd import harness
 
     w = WORKLOADS[args.workload]
+    if args.layers:
+        w = w.with_(n_layers=args.layers, name=f"{w.name}[{args.layers} layers]")
     t_setup = time.perf_counter()
     st = harness.DeviceStack(w)
     for name, val in (("gemm_workgroups_in", args.gemm_wg_in), ("gemm_workgroups_out", args.gemm_wg_out),
-                      ("attn_blocks_per_split", args.attn_bps)):
+                      ("attn_blocks_per_split", args.attn_bps), ("act_digits", args.act_digits)):
         if val:
             st.dec.set_option(name, val)
     torch.cuda.synchronize()

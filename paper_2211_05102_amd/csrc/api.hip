@@ -59,7 +59,7 @@ pd_status check_batch(int32_t B, int32_t L_ctx) {
 
 // offsets inside one packed layer
 struct PackedLayout {
-    size_t w_in, w_out, s_in, s_out, gamma, total;
+    size_t w_in, w_out, s_in, s_out, gamma, gamma_absmax, total;
 };
 PackedLayout packed_layout(const Shape& s) {
     PackedLayout p;
@@ -69,12 +69,15 @@ PackedLayout packed_layout(const Shape& s) {
     p.s_in = o; o += align256((size_t)s.n_in * 4);
     p.s_out = o; o += align256((size_t)s.d * 4);
     p.gamma = o; o += align256((size_t)s.d * 4);
+    p.gamma_absmax = o; o += 256;  // max |gamma|, one float
     p.total = o;
     return p;
 }
 
 int auto_bps(int B, int L_ctx) {
-    long long v = (long long)(L_ctx / 32) * B / 512;
+    // one workgroup per compute unit when the batch allows: each wave then streams
+    // several blocks back to back, which is what keeps its load ring full
+    long long v = (long long)(L_ctx / 32) * B / 256;
     if (v < PD_MIN_BLOCKS_PER_SPLIT) v = PD_MIN_BLOCKS_PER_SPLIT;
     if (v > 64) v = 64;
     return (int)v;
@@ -97,7 +100,7 @@ GemmPlan gemm_plan(const Shape& s, int B, int g_in_opt, int g_out_opt) {
 
 // workspace carving; sized for the largest slot counts so options never overflow it
 struct Workspace {
-    size_t flag, cs, xres, h, hs, part_in, q, act, acts, opart, ml, part_out, total;
+    size_t flag, cs, xres, h, hs, part_in, q, act, acts, opart, ml, part_out, stats, total;
 };
 Workspace workspace_layout(const Shape& s, int B, int L_ctx) {
     Workspace w;
@@ -115,6 +118,7 @@ Workspace workspace_layout(const Shape& s, int B, int L_ctx) {
     w.opart = o; o += align256((size_t)B * nsplit_max * s.H * s.dh * 4);
     w.ml = o; o += align256((size_t)B * nsplit_max * s.H * 2 * 4);
     w.part_out = o; o += align256((size_t)PD_MAX_SPLITS * B * s.d * 4);
+    w.stats = o; o += align256((size_t)B * ((s.d + 1023) / 1024) * 4 * 4);  // LayerNorm slice statistics
     w.total = o;
     return w;
 }
@@ -179,6 +183,7 @@ pd_status run_layers(pd_handle* h, const StepArgs& a, hipStream_t st) {
     const int B = a.B;
     float* cs = reinterpret_cast<float*>(a.ws + w.cs);
     int32_t* flag = reinterpret_cast<int32_t*>(a.ws + w.flag);
+    float* stats = reinterpret_cast<float*>(a.ws + w.stats);
     float* xres = reinterpret_cast<float*>(a.ws + w.xres);
     unsigned char* hq = a.ws + w.h;
     float* hs = reinterpret_cast<float*>(a.ws + w.hs);
@@ -199,7 +204,7 @@ pd_status run_layers(pd_handle* h, const StepArgs& a, hipStream_t st) {
     const int c_in = s.d / 128, c_attn = s.H * s.dh / 128, c_ffn = s.F / 128;
     const int blk_ln = c_in < 1024 ? c_in : 1024;
     const int blk_o = c_attn < 16 ? c_attn : 16;
-    const int blk_a = c_ffn < 64 ? c_ffn : 64;
+    const int blk_a = c_ffn < 16 ? c_ffn : 16;
     const int bps = h->opt_bps > 0 ? h->opt_bps : auto_bps(B, a.L_ctx);
     const int nd = h->act_digits;
     const size_t kv_layer_bytes = kv_layer_elems(s, B, a.L_ctx) * 2;
@@ -232,11 +237,14 @@ pd_status run_layers(pd_handle* h, const StepArgs& a, hipStream_t st) {
         const bool last = i == a.n_run - 1;
         prof_mark(h, PROF_EPI_OUT, st);
         PD_TRY_HIP(pd::launch_residual(part_out, pl_out, s_out, xres, B, s.d, a.add_residual,
-                                       last ? a.x_out_bf16 : nullptr, last ? a.y_out_f32 : nullptr, st),
+                                       last ? a.x_out_bf16 : nullptr, last ? a.y_out_f32 : nullptr,
+                                       last ? nullptr : stats, st),
                    "residual");
         if (!last) {
-            const float* gamma_next = reinterpret_cast<const float*>(L + pl.total + pl.gamma);
-            PD_TRY_HIP(pd::launch_ln(xres, gamma_next, B, s.d, h->desc.ln_eps, hq, hs, nd, st), "ln");
+            const unsigned char* Ln = L + pl.total;
+            PD_TRY_HIP(pd::launch_ln_slices(xres, reinterpret_cast<const float*>(Ln + pl.gamma),
+                                            reinterpret_cast<const float*>(Ln + pl.gamma_absmax), stats, B, s.d,
+                                            h->desc.ln_eps, hq, hs, nd, st), "ln");
         }
         prof_mark(h, PROF_EPI_OUT, st);
     }
@@ -401,6 +409,8 @@ pd_status pd_pack_layer(pd_handle* h, const int8_t* w_in, const uint16_t* s_in, 
     PD_TRY_HIP(pd::launch_pack_vector(s_in, reinterpret_cast<float*>(dst + pl.s_in), s.n_in, 1, s.n_qkv, s.F, st), "pack s_in");
     PD_TRY_HIP(pd::launch_pack_vector(s_out, reinterpret_cast<float*>(dst + pl.s_out), s.d, 0, 0, 0, st), "pack s_out");
     PD_TRY_HIP(pd::launch_pack_vector(gamma, reinterpret_cast<float*>(dst + pl.gamma), s.d, 0, 0, 0, st), "pack gamma");
+    PD_TRY_HIP(pd::launch_vec_absmax(reinterpret_cast<const float*>(dst + pl.gamma), s.d,
+                                     reinterpret_cast<float*>(dst + pl.gamma_absmax), st), "gamma absmax");
     return PD_OK;
 }
 

@@ -26,12 +26,142 @@
 // and P would be the largest error of the whole step.
 // Split-KV: workgroup (split, b) takes `bps` consecutive 32-token blocks, its 4
 // waves take them round-robin with a running (max, sum, acc) each (base-2
-// exponentials, Section 3.5), merge through LDS, and write one fp32 partial; a
+// exponentials, Section 3.5), merge through LDS, and write one fp32 partial; the
 // second kernel combines the partials of a sequence in fixed order.
 #include "common.h"
 #include "kernels.h"
 
 namespace pd {
+
+// o[b][h*dh + c] = sum_s w_s O_s[c] / sum_s w_s l_s,  w_s = 2^(m_s - max m), splits in index order.
+// One workgroup per scale block of the row (blk_o chunks of 128 elements, at most
+// 16); each wave takes every fourth chunk, two adjacent channels per lane.  The
+// result goes out as fp32 (`o`) and/or in block fixed point as the first
+// H*dh/128 chunks of the output projection's operand (`actq`, `acts`).
+// MAXS: upper bound of the live splits, so that every load of the sums below is
+// issued before any is needed.
+template <int MAXS>
+__global__ __launch_bounds__(256) void mqa_combine_kernel(
+    const float* __restrict__ opart, const float* __restrict__ ml,
+    const int32_t* __restrict__ positions, int H, int dh, int L_ctx, int bps, int nsplit,
+    float* __restrict__ o, unsigned char* __restrict__ actq, float* __restrict__ acts,
+    int k_out, int blk_o, int nd) {
+    __shared__ float red[4];
+    const int b = blockIdx.y;
+    const int P = positions[b];
+    if (P < 0 || P >= L_ctx) return;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int c_lo = blockIdx.x * blk_o;
+    const int c_hi = c_lo + blk_o < (H * dh >> 7) ? c_lo + blk_o : (H * dh >> 7);
+    const int live = ((P >> 5) + bps) / bps;  // ceil(nblk / bps), nblk = P/32 + 1
+    float o0[4], o1[4], mx = 0.f;
+#pragma unroll
+    for (int k = 0; k < 4; k++) {
+        const int j = c_lo + wave + 4 * k;
+        o0[k] = o1[k] = 0.f;
+        if (j < c_hi) {
+            const int idx = j * QCHUNK + 2 * lane;  // idx and idx + 1 lie in the same head
+            const int h = idx / dh, c = idx - h * dh;
+            const size_t row0 = (size_t)b * nsplit * H + h;
+            f32x2 mlv[MAXS], ov[MAXS];
+#pragma unroll
+            for (int s = 0; s < MAXS; s++) {
+                const size_t row = row0 + (size_t)(s < live ? s : live - 1) * H;
+                mlv[s] = *reinterpret_cast<const f32x2*>(ml + row * 2);
+                ov[s] = *reinterpret_cast<const f32x2*>(opart + row * dh + c);
+            }
+            float m_all = -INFINITY;
+#pragma unroll
+            for (int s = 0; s < MAXS; s++)
+                if (s < live) m_all = fmaxf(m_all, mlv[s].x);
+            float n0 = 0.f, n1 = 0.f, den = 0.f;
+#pragma unroll
+            for (int s = 0; s < MAXS; s++)
+                if (s < live) {
+                    const float w = __builtin_amdgcn_exp2f(mlv[s].x - m_all);
+                    den += w * mlv[s].y;
+                    n0 += w * ov[s].x;
+                    n1 += w * ov[s].y;
+                }
+            o0[k] = n0 / den;
+            o1[k] = n1 / den;
+            mx = fmaxf(mx, fmaxf(fabsf(o0[k]), fabsf(o1[k])));
+            if (o) {
+                const f32x2 out = {o0[k], o1[k]};
+                *reinterpret_cast<f32x2*>(o + (size_t)b * H * dh + idx) = out;
+            }
+        }
+    }
+    if (!actq) return;
+    const float s = qscale_from_max(block_max_256(mx, red), nd);
+    const float inv = 1.0f / s;
+#pragma unroll
+    for (int k = 0; k < 4; k++) {
+        const int j = c_lo + wave + 4 * k;
+        if (j < c_hi) {
+            quantize_pair_store(o0[k], o1[k], inv, nd, lane,
+                                actq + ((size_t)b * k_out + (size_t)j * QCHUNK) * nd);
+            if (lane == 0) acts[(size_t)j * QSCALE_ROWS + b] = s;
+        }
+    }
+}
+
+// the same with a run-time number of splits (long contexts with small splits)
+__global__ __launch_bounds__(256) void mqa_combine_any_kernel(
+    const float* __restrict__ opart, const float* __restrict__ ml,
+    const int32_t* __restrict__ positions, int H, int dh, int L_ctx, int bps, int nsplit,
+    float* __restrict__ o, unsigned char* __restrict__ actq, float* __restrict__ acts,
+    int k_out, int blk_o, int nd) {
+    __shared__ float red[4];
+    const int b = blockIdx.y;
+    const int P = positions[b];
+    if (P < 0 || P >= L_ctx) return;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int c_lo = blockIdx.x * blk_o;
+    const int c_hi = c_lo + blk_o < (H * dh >> 7) ? c_lo + blk_o : (H * dh >> 7);
+    const int live = ((P >> 5) + bps) / bps;
+    float o0[4], o1[4], mx = 0.f;
+#pragma unroll
+    for (int k = 0; k < 4; k++) {
+        const int j = c_lo + wave + 4 * k;
+        o0[k] = o1[k] = 0.f;
+        if (j < c_hi) {
+            const int idx = j * QCHUNK + 2 * lane;
+            const int h = idx / dh, c = idx - h * dh;
+            const size_t row0 = (size_t)b * nsplit * H + h;
+            float m_all = -INFINITY;
+            for (int s = 0; s < live; s++) m_all = fmaxf(m_all, ml[(row0 + (size_t)s * H) * 2]);
+            float n0 = 0.f, n1 = 0.f, den = 0.f;
+            for (int s = 0; s < live; s++) {
+                const size_t row = row0 + (size_t)s * H;
+                const float w = __builtin_amdgcn_exp2f(ml[row * 2] - m_all);
+                den += w * ml[row * 2 + 1];
+                const f32x2 ov = *reinterpret_cast<const f32x2*>(opart + row * dh + c);
+                n0 += w * ov.x;
+                n1 += w * ov.y;
+            }
+            o0[k] = n0 / den;
+            o1[k] = n1 / den;
+            mx = fmaxf(mx, fmaxf(fabsf(o0[k]), fabsf(o1[k])));
+            if (o) {
+                const f32x2 out = {o0[k], o1[k]};
+                *reinterpret_cast<f32x2*>(o + (size_t)b * H * dh + idx) = out;
+            }
+        }
+    }
+    if (!actq) return;
+    const float s = qscale_from_max(block_max_256(mx, red), nd);
+    const float inv = 1.0f / s;
+#pragma unroll
+    for (int k = 0; k < 4; k++) {
+        const int j = c_lo + wave + 4 * k;
+        if (j < c_hi) {
+            quantize_pair_store(o0[k], o1[k], inv, nd, lane,
+                                actq + ((size_t)b * k_out + (size_t)j * QCHUNK) * nd);
+            if (lane == 0) acts[(size_t)j * QSCALE_ROWS + b] = s;
+        }
+    }
+}
 
 template <int DH>
 __global__ __launch_bounds__(256) void mqa_attend_kernel(
@@ -77,8 +207,14 @@ __global__ __launch_bounds__(256) void mqa_attend_kernel(
     }
     __syncthreads();
 
-    const uint4* kbase = kc + (size_t)b * nblk_cap * BLK_U4 + lane;
-    const uint4* vbase = vc + (size_t)b * nblk_cap * BLK_U4 + lane;
+    // K and V of this sequence as buffers that end where this workgroup's share
+    // ends: the software pipeline below always asks for the next block, and a read
+    // past the end returns zeros without touching memory.
+    const __amdgpu_buffer_rsrc_t k_rs = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint4*>(kc + (size_t)b * nblk_cap * BLK_U4), 0, blk1 * BLK_U4 * 16, 0x00020000);
+    const __amdgpu_buffer_rsrc_t v_rs = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint4*>(vc + (size_t)b * nblk_cap * BLK_U4), 0, blk1 * BLK_U4 * 16, 0x00020000);
+    const uint32_t lane16 = lane * 16;
 
     float m_run = -INFINITY, l_run = 0.f;
     f32x16 O[DB];
@@ -87,27 +223,29 @@ __global__ __launch_bounds__(256) void mqa_attend_kernel(
 #pragma unroll
         for (int r = 0; r < 16; r++) O[db][r] = 0.f;
 
-    for (int blk = blk0 + wave; blk < blk1; blk += 4) {
-        uint4 kreg[KJ], vreg[DB][2];
-        const uint4* kp = kbase + (size_t)blk * BLK_U4;
-        const uint4* vp = vbase + (size_t)blk * BLK_U4;
+    // One ring of KJ 1-KiB pieces per wave, always full: the K pieces of a block are
+    // consumed in order and each slot is refilled at once with the V piece of the
+    // same index; the V pieces are consumed in order and refilled with the K pieces
+    // of this wave's next block.  Non-temporal: every byte is used once.
+    u32x4 ring[KJ];
+    const int first = blk0 + wave;
 #pragma unroll
-        for (int j = 0; j < KJ; j++) kreg[j] = ld_stream(kp + j * 64);
-#pragma unroll
-        for (int db = 0; db < DB; db++)
-#pragma unroll
-            for (int kk = 0; kk < 2; kk++) vreg[db][kk] = ld_stream(vp + (db * 2 + kk) * 64);
+    for (int j = 0; j < KJ; j++)
+        ring[j] = __builtin_amdgcn_raw_buffer_load_b128(k_rs, lane16, (first * BLK_U4 + j * 64) * 16, 2);
 
+    for (int blk = first; blk < blk1; blk += 4) {
+        const int blk_off = blk * BLK_U4 * 16, next_off = (blk + 4) * BLK_U4 * 16;
         f32x16 S;
 #pragma unroll
         for (int r = 0; r < 16; r++) S[r] = 0.f;
 #pragma unroll
         for (int j = 0; j < KJ; j++) {
-            const bf16x8 kop = __builtin_bit_cast(bf16x8, kreg[j]);
+            const bf16x8 kop = __builtin_bit_cast(bf16x8, ring[j]);
             S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
                 kop, __builtin_bit_cast(bf16x8, smem[j * 64 + lane]), S, 0, 0, 0);
             S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
                 kop, __builtin_bit_cast(bf16x8, smem[(KJ + j) * 64 + lane]), S, 0, 0, 0);
+            ring[j] = __builtin_amdgcn_raw_buffer_load_b128(v_rs, lane16, blk_off + j * 1024, 2);
         }
         const bool tail = (blk == nblk - 1) && ((P & 31) != 31);
         if (tail) {
@@ -116,19 +254,6 @@ __global__ __launch_bounds__(256) void mqa_attend_kernel(
                 int t = blk * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
                 if (t > P) S[r] = -INFINITY;
             }
-            // slots past P may hold anything (even NaN); p is exactly 0 there, so zero V too
-#pragma unroll
-            for (int db = 0; db < DB; db++)
-#pragma unroll
-                for (int kk = 0; kk < 2; kk++) {
-                    uint32_t w[4] = {vreg[db][kk].x, vreg[db][kk].y, vreg[db][kk].z, vreg[db][kk].w};
-#pragma unroll
-                    for (int e = 0; e < 8; e++) {
-                        int t = blk * 32 + 16 * kk + 8 * (e >> 2) + 4 * g + (e & 3);
-                        if (t > P) w[e >> 1] &= (e & 1) ? 0x0000ffffu : 0xffff0000u;
-                    }
-                    vreg[db][kk] = make_uint4(w[0], w[1], w[2], w[3]);
-                }
         }
         float mloc = S[0];
 #pragma unroll
@@ -167,9 +292,22 @@ __global__ __launch_bounds__(256) void mqa_attend_kernel(
         for (int db = 0; db < DB; db++)
 #pragma unroll
             for (int kk = 0; kk < 2; kk++) {
-                const bf16x8 vop = __builtin_bit_cast(bf16x8, vreg[db][kk]);
+                u32x4 vr = ring[db * 2 + kk];
+                if (tail) {
+                    // slots past P may hold anything (even NaN); p is exactly 0 there, so zero V too
+                    uint32_t w[4] = {vr.x, vr.y, vr.z, vr.w};
+#pragma unroll
+                    for (int e = 0; e < 8; e++) {
+                        int t = blk * 32 + 16 * kk + 8 * (e >> 2) + 4 * g + (e & 3);
+                        if (t > P) w[e >> 1] &= (e & 1) ? 0x0000ffffu : 0xffff0000u;
+                    }
+                    vr.x = w[0]; vr.y = w[1]; vr.z = w[2]; vr.w = w[3];
+                }
+                const bf16x8 vop = __builtin_bit_cast(bf16x8, vr);
                 O[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop, pop[kk][0], O[db], 0, 0, 0);
                 O[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vop, pop[kk][1], O[db], 0, 0, 0);
+                ring[db * 2 + kk] =
+                    __builtin_amdgcn_raw_buffer_load_b128(k_rs, lane16, next_off + (db * 2 + kk) * 1024, 2);
             }
     }
     __syncthreads();  // every wave is done with the q operands: smem becomes the merge buffer
@@ -221,67 +359,7 @@ __global__ __launch_bounds__(256) void mqa_attend_kernel(
                 *reinterpret_cast<f32x4*>(orow + db * 32 + 8 * i + 4 * g) = v;
             }
     }
-}
 
-// o[b][h*dh + c] = sum_s w_s O_s[c] / sum_s w_s l_s,  w_s = 2^(m_s - max m), splits in index order.
-// One workgroup per scale block of the row (blk_o chunks of 128 elements, at most
-// 16); each wave takes every fourth chunk, two adjacent channels per lane.  The
-// result goes out as fp32 (`o`) and/or in block fixed point as the first
-// H*dh/128 chunks of the output projection's operand (`actq`, `acts`).
-__global__ __launch_bounds__(256) void mqa_combine_kernel(
-    const float* __restrict__ opart, const float* __restrict__ ml,
-    const int32_t* __restrict__ positions, int H, int dh, int L_ctx, int bps, int nsplit,
-    float* __restrict__ o, unsigned char* __restrict__ actq, float* __restrict__ acts,
-    int k_out, int blk_o, int nd) {
-    __shared__ float red[4];
-    const int b = blockIdx.y;
-    const int P = positions[b];
-    if (P < 0 || P >= L_ctx) return;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int c_lo = blockIdx.x * blk_o;
-    const int c_hi = c_lo + blk_o < (H * dh >> 7) ? c_lo + blk_o : (H * dh >> 7);
-    const int live = ((P >> 5) + bps) / bps;  // ceil(nblk / bps), nblk = P/32 + 1
-    float o0[4], o1[4], mx = 0.f;
-#pragma unroll
-    for (int k = 0; k < 4; k++) {
-        const int j = c_lo + wave + 4 * k;
-        o0[k] = o1[k] = 0.f;
-        if (j < c_hi) {
-            const int idx = j * QCHUNK + 2 * lane;  // idx and idx + 1 lie in the same head
-            const int h = idx / dh, c = idx - h * dh;
-            const size_t row0 = (size_t)b * nsplit * H + h;
-            float m_all = -INFINITY;
-            for (int s = 0; s < live; s++) m_all = fmaxf(m_all, ml[(row0 + (size_t)s * H) * 2]);
-            float n0 = 0.f, n1 = 0.f, den = 0.f;
-            for (int s = 0; s < live; s++) {
-                const size_t row = row0 + (size_t)s * H;
-                const float w = __builtin_amdgcn_exp2f(ml[row * 2] - m_all);
-                den += w * ml[row * 2 + 1];
-                const f32x2 ov = *reinterpret_cast<const f32x2*>(opart + row * dh + c);
-                n0 += w * ov.x;
-                n1 += w * ov.y;
-            }
-            o0[k] = n0 / den;
-            o1[k] = n1 / den;
-            mx = fmaxf(mx, fmaxf(fabsf(o0[k]), fabsf(o1[k])));
-            if (o) {
-                const f32x2 ov = {o0[k], o1[k]};
-                *reinterpret_cast<f32x2*>(o + (size_t)b * H * dh + idx) = ov;
-            }
-        }
-    }
-    if (!actq) return;
-    const float s = qscale_from_max(block_max_256(mx, red), nd);
-    const float inv = 1.0f / s;
-#pragma unroll
-    for (int k = 0; k < 4; k++) {
-        const int j = c_lo + wave + 4 * k;
-        if (j < c_hi) {
-            quantize_pair_store(o0[k], o1[k], inv, nd, lane,
-                                actq + ((size_t)b * k_out + (size_t)j * QCHUNK) * nd);
-            if (lane == 0) acts[(size_t)j * QSCALE_ROWS + b] = s;
-        }
-    }
 }
 
 // canonical [B][L_ctx][dh]  <->  library block layout, one element per thread
@@ -332,9 +410,13 @@ hipError_t launch_mqa_attend(const float* q, const void* kc_layer, const void* v
         return hipErrorInvalidValue;
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    mqa_combine_kernel<<<dim3((H * dh / 128 + blk_o - 1) / blk_o, B), block, 0, stream>>>(
-        opart, ml, positions, H, dh, L_ctx, bps, nsplit, o, reinterpret_cast<unsigned char*>(actq),
-        acts, k_out, blk_o, nd);
+    dim3 cgrid((H * dh / 128 + blk_o - 1) / blk_o, B);
+    unsigned char* aq = reinterpret_cast<unsigned char*>(actq);
+#define PD_COMB(K) K<<<cgrid, block, 0, stream>>>(opart, ml, positions, H, dh, L_ctx, bps, nsplit, o, aq, acts, k_out, blk_o, nd)
+    if (nsplit <= 4) PD_COMB(mqa_combine_kernel<4>);
+    else if (nsplit <= 8) PD_COMB(mqa_combine_kernel<8>);
+    else PD_COMB(mqa_combine_any_kernel);
+#undef PD_COMB
     return hipGetLastError();
 }
 

@@ -39,14 +39,16 @@ hipError_t launch_prep(const int32_t* positions, int B, int L_ctx, int dh, float
                        float* cs, int32_t* flag, hipStream_t stream);
 hipError_t launch_ln_first(const uint16_t* x_in, const float* gamma, int B, int d, float eps,
                            float* xres, void* hq, float* hs, int nd, hipStream_t stream);
-hipError_t launch_ln(const float* xres, const float* gamma, int B, int d, float eps, void* hq,
-                     float* hs, int nd, hipStream_t stream);
 hipError_t launch_epi_in(const float* part, SkqPlan pl, const float* scale, const float* cs,
                          const int32_t* positions, int B, int H, int dh, int F, int L_ctx,
                          float* q, void* kc_layer, void* vc_layer, void* actq, float* acts,
                          int blk_a, int nd, hipStream_t stream);
 hipError_t launch_residual(const float* part, SkqPlan pl, const float* scale, float* xres, int B,
                            int d, int add_residual, uint16_t* x_out_bf16, float* y_out_f32,
-                           hipStream_t stream);
+                           float* stats, hipStream_t stream);
+hipError_t launch_ln_slices(const float* xres, const float* gamma, const float* gamma_absmax,
+                            const float* stats, int B, int d, float eps, void* hq, float* hs,
+                            int nd, hipStream_t stream);
+hipError_t launch_vec_absmax(const float* v, int n, float* out, hipStream_t stream);
 
 }  // namespace pd

@@ -6,8 +6,9 @@
 //   epi_in     : sum K-split partials of the input projection, apply the per-channel
 //                scale (Section 3.6), rotate q and k, append k/v to the cache,
 //                SwiGLU gate (Section 3.5 names the base-2 Swish)
-//   residual   : sum partials of the output projection, scale, add the residual
-//   ln         : LayerNorm of the updated residual for the next layer
+//   residual   : sum partials of the output projection, scale, add the residual; slice
+//                statistics of the updated rows
+//   ln_slices  : LayerNorm of the updated residual for the next layer
 // Operands of the projections (LayerNorm output, SwiGLU output) leave these
 // kernels in block fixed point (common.h), one wavefront per 128-element chunk.
 #include "common.h"
@@ -83,19 +84,6 @@ __global__ __launch_bounds__(256) void ln_first_kernel(const uint16_t* __restric
         sum += v;
     }
     __syncthreads();  // the row is re-read with a different thread mapping below
-    layernorm_row(xrow, gamma, d, eps, sum, b, nd, hq, hs, red);
-}
-
-// LayerNorm of the fp32 residual stream for the next layer
-__global__ __launch_bounds__(256) void ln_kernel(const float* __restrict__ xres,
-                                                 const float* __restrict__ gamma, int d, float eps,
-                                                 unsigned char* __restrict__ hq,
-                                                 float* __restrict__ hs, int nd) {
-    __shared__ float red[4];
-    const int b = blockIdx.x, tid = threadIdx.x;
-    const float* xrow = xres + (size_t)b * d;
-    float sum = 0.f;
-    for (int c = tid; c < d; c += 256) sum += xrow[c];
     layernorm_row(xrow, gamma, d, eps, sum, b, nd, hq, hs, red);
 }
 
@@ -211,28 +199,102 @@ __global__ __launch_bounds__(256) void epi_in_kernel(
     }
 }
 
-// x' = [x +] scale * sum over slots of part   (elementwise; slots summed in index order)
+// x' = [x +] scale * sum over slots of part   (elementwise; slots summed in index order).
+// If `stats` is given, every workgroup also leaves (mean, M2, max |x - mean|) of its
+// 1024-column slice of the updated row for the LayerNorm kernel that follows.
 __global__ __launch_bounds__(256) void residual_kernel(const float* __restrict__ part, SkqPlan pl,
                                                        const float* __restrict__ scale,
                                                        float* __restrict__ xres, int B, int d,
                                                        int add_residual,
                                                        uint16_t* __restrict__ x_out_bf16,
-                                                       float* __restrict__ y_out_f32) {
-    const int b = blockIdx.y, c = (blockIdx.x * 256 + threadIdx.x) * 4;
-    if (c >= d) return;
+                                                       float* __restrict__ y_out_f32,
+                                                       float* __restrict__ stats) {
+    __shared__ float red[4];
+    const int tid = threadIdx.x, b = blockIdx.y, c = (blockIdx.x * 256 + tid) * 4;
+    const bool in = c < d;
     const size_t stride = (size_t)B * d, off = (size_t)b * d + c;
-    const int ns = skq_slots(c / pl.tile_cols, pl.C, pl.T, pl.G);  // 4 columns share a tile
-    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-    for (int s = 0; s < ns; s++) acc += *reinterpret_cast<const f32x4*>(part + (size_t)s * stride + off);
-    const f32x4 sc = *reinterpret_cast<const f32x4*>(scale + c);
-    f32x4 xn = sc * acc;
-    if (add_residual) xn += *reinterpret_cast<const f32x4*>(xres + off);
-    *reinterpret_cast<f32x4*>(xres + off) = xn;
-    if (y_out_f32) *reinterpret_cast<f32x4*>(y_out_f32 + off) = xn;
-    if (x_out_bf16) {
-        uint2 o = {pack_bf16x2(xn.x, xn.y), pack_bf16x2(xn.z, xn.w)};
-        *reinterpret_cast<uint2*>(x_out_bf16 + off) = o;
+    f32x4 xn = {0.f, 0.f, 0.f, 0.f};
+    if (in) {
+        const int ns = skq_slots(c / pl.tile_cols, pl.C, pl.T, pl.G);  // 4 columns share a tile
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+        for (int s = 0; s < ns; s++) acc += *reinterpret_cast<const f32x4*>(part + (size_t)s * stride + off);
+        const f32x4 sc = *reinterpret_cast<const f32x4*>(scale + c);
+        xn = sc * acc;
+        if (add_residual) xn += *reinterpret_cast<const f32x4*>(xres + off);
+        *reinterpret_cast<f32x4*>(xres + off) = xn;
+        if (y_out_f32) *reinterpret_cast<f32x4*>(y_out_f32 + off) = xn;
+        if (x_out_bf16) {
+            uint2 o = {pack_bf16x2(xn.x, xn.y), pack_bf16x2(xn.z, xn.w)};
+            *reinterpret_cast<uint2*>(x_out_bf16 + off) = o;
+        }
     }
+    if (!stats) return;
+    const int n_here = d - (int)blockIdx.x * 1024 < 1024 ? d - (int)blockIdx.x * 1024 : 1024;
+    const float mean_s = block_sum_256(in ? (xn.x + xn.y) + (xn.z + xn.w) : 0.f, red) / (float)n_here;
+    const f32x4 dv = xn - mean_s;
+    const float m2_s = block_sum_256(in ? (dv.x * dv.x + dv.y * dv.y) + (dv.z * dv.z + dv.w * dv.w) : 0.f, red);
+    const float dev_s = block_max_256(
+        in ? fmaxf(fmaxf(fabsf(dv.x), fabsf(dv.y)), fmaxf(fabsf(dv.z), fabsf(dv.w))) : 0.f, red);
+    if (tid == 0) {
+        float* st = stats + ((size_t)b * gridDim.x + blockIdx.x) * 4;
+        st[0] = mean_s;
+        st[1] = m2_s;
+        st[2] = dev_s;
+    }
+}
+
+// LayerNorm of the updated residual row for the next layer, one workgroup per
+// 1024-column slice.  Every workgroup merges the slice statistics of its row in
+// index order (pairwise update of count, mean, M2), so all of them get the same
+// mean and variance bit for bit.  The row's single power-of-two scale comes from a
+// bound instead of the exact maximum, so that no second pass over the row is
+// needed:  |h| <= max|gamma| * max_s(maxdev_s + |mean_s - mean|) / sigma; the bound
+// costs at most a bit or two of the 23 that three digit planes carry.
+__global__ __launch_bounds__(256) void ln_slices_kernel(const float* __restrict__ xres,
+                                                        const float* __restrict__ gamma,
+                                                        const float* __restrict__ gamma_absmax,
+                                                        const float* __restrict__ stats, int d,
+                                                        float eps, unsigned char* __restrict__ hq,
+                                                        float* __restrict__ hs, int nd) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int b = blockIdx.y, nsl = gridDim.x;
+    float n_tot = 0.f, mean = 0.f, m2 = 0.f;
+    for (int sl = 0; sl < nsl; sl++) {
+        const float n_i = (float)(d - sl * 1024 < 1024 ? d - sl * 1024 : 1024);
+        const float* st = stats + ((size_t)b * nsl + sl) * 4;
+        const float delta = st[0] - mean, n_new = n_tot + n_i;
+        mean += delta * (n_i / n_new);
+        m2 += st[1] + delta * delta * (n_tot * n_i / n_new);
+        n_tot = n_new;
+    }
+    float dev = 0.f;
+    for (int sl = 0; sl < nsl; sl++) {
+        const float* st = stats + ((size_t)b * nsl + sl) * 4;
+        dev = fmaxf(dev, st[2] + fabsf(st[0] - mean));
+    }
+    const float rstd = 1.0f / sqrtf(m2 / (float)d + eps);
+    const float s = qscale_from_max(gamma_absmax[0] * dev * rstd * 1.0001f, nd);
+    const float inv = 1.0f / s;
+    const float* xrow = xres + (size_t)b * d;
+    const int j_end = (blockIdx.x * 8 + 8) < (d >> 7) ? (blockIdx.x * 8 + 8) : (d >> 7);
+    for (int j = blockIdx.x * 8 + wave; j < j_end; j += 4) {
+        const int cc = j * QCHUNK + 2 * lane;
+        const f32x2 xv = *reinterpret_cast<const f32x2*>(xrow + cc);
+        const f32x2 gv = *reinterpret_cast<const f32x2*>(gamma + cc);
+        quantize_pair_store(gv.x * (xv.x - mean) * rstd, gv.y * (xv.y - mean) * rstd, inv, nd, lane,
+                            hq + ((size_t)b * d + (size_t)j * QCHUNK) * nd);
+        if (lane == 0) hs[(size_t)j * QSCALE_ROWS + b] = s;
+    }
+}
+
+// max |v[i]| of an fp32 vector (pack time: the LayerNorm gain of a layer)
+__global__ __launch_bounds__(256) void vec_absmax_kernel(const float* __restrict__ v, int n,
+                                                         float* __restrict__ out) {
+    __shared__ float red[4];
+    float mx = 0.f;
+    for (int i = threadIdx.x; i < n; i += 256) mx = fmaxf(mx, fabsf(v[i]));
+    mx = block_max_256(mx, red);
+    if (threadIdx.x == 0) out[0] = mx;
 }
 
 hipError_t launch_prep(const int32_t* positions, int B, int L_ctx, int dh, float rope_base,
@@ -245,13 +307,6 @@ hipError_t launch_ln_first(const uint16_t* x_in, const float* gamma, int B, int 
                            float* xres, void* hq, float* hs, int nd, hipStream_t stream) {
     ln_first_kernel<<<dim3(B), dim3(256), 0, stream>>>(x_in, gamma, d, eps, xres,
                                                        reinterpret_cast<unsigned char*>(hq), hs, nd);
-    return hipGetLastError();
-}
-
-hipError_t launch_ln(const float* xres, const float* gamma, int B, int d, float eps, void* hq,
-                     float* hs, int nd, hipStream_t stream) {
-    ln_kernel<<<dim3(B), dim3(256), 0, stream>>>(xres, gamma, d, eps,
-                                                 reinterpret_cast<unsigned char*>(hq), hs, nd);
     return hipGetLastError();
 }
 
@@ -272,9 +327,22 @@ hipError_t launch_epi_in(const float* part, SkqPlan pl, const float* scale, cons
 
 hipError_t launch_residual(const float* part, SkqPlan pl, const float* scale, float* xres, int B,
                            int d, int add_residual, uint16_t* x_out_bf16, float* y_out_f32,
-                           hipStream_t stream) {
+                           float* stats, hipStream_t stream) {
     residual_kernel<<<dim3((d / 4 + 255) / 256, B), dim3(256), 0, stream>>>(
-        part, pl, scale, xres, B, d, add_residual, x_out_bf16, y_out_f32);
+        part, pl, scale, xres, B, d, add_residual, x_out_bf16, y_out_f32, stats);
+    return hipGetLastError();
+}
+
+hipError_t launch_ln_slices(const float* xres, const float* gamma, const float* gamma_absmax,
+                            const float* stats, int B, int d, float eps, void* hq, float* hs,
+                            int nd, hipStream_t stream) {
+    ln_slices_kernel<<<dim3((d + 1023) / 1024, B), dim3(256), 0, stream>>>(
+        xres, gamma, gamma_absmax, stats, d, eps, reinterpret_cast<unsigned char*>(hq), hs, nd);
+    return hipGetLastError();
+}
+
+hipError_t launch_vec_absmax(const float* v, int n, float* out, hipStream_t stream) {
+    vec_absmax_kernel<<<dim3(1), dim3(256), 0, stream>>>(v, n, out);
     return hipGetLastError();
 }
 

@@ -457,7 +457,7 @@ hipError_t launch_qgemm(const void* wp, const void* qa, const float* scale_t, fl
     if (blk0 < 1 || blk0 > 1024 || blk1 < 1 || blk1 > 1024 || c_split < 0 || c_split > K / 128)
         return hipErrorInvalidValue;
     if (bm == 1) PD_LAUNCH(1, 1, 6);
-    else PD_LAUNCH(2, 1, 4);
+    else PD_LAUNCH(2, 1, 2);
 #undef PD_LAUNCH
     return hipGetLastError();
 }
