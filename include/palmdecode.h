@@ -103,8 +103,8 @@ pd_status pd_workspace_bytes(const pd_model_desc* desc, int32_t B, int32_t L_ctx
 pd_status pd_create(const pd_model_desc* desc, pd_handle** out);
 pd_status pd_destroy(pd_handle* h);
 /* Tuning knobs: "gemm_workgroups_in", "gemm_workgroups_out" (workgroups that
- * share the weight matrix of the input / output projection, 0 = automatic: one
- * per compute unit), "attn_blocks_per_split" (32-token blocks per attention
+ * share the weight matrix of the input / output projection, 0 = automatic:
+ * two per compute unit; values above the automatic count are rejected), "attn_blocks_per_split" (32-token blocks per attention
  * workgroup, 0 = automatic), "act_digits" (2 or 3 int8 digit planes per
  * projection operand), "profile_kernel" (see pd_profile_read).  Unknown names
  * return PD_ERR_RANGE. */
@@ -187,7 +187,7 @@ pd_status pd_check_async(pd_handle* h, void* workspace, void* stream);
  *   matrix is shared between; the result is bit-reproducible for a given value.
  *   The activations are converted to the library's 3-digit block fixed point
  *   (23 bits relative to each 128-element chunk's maximum) before the product. */
-pd_status pd_qgemm_workspace_bytes(int32_t B, int32_t K, int32_t N, size_t* bytes);
+pd_status pd_qgemm_workspace_bytes(int32_t B, int32_t K, int32_t N, int32_t workgroups, size_t* bytes);
 pd_status pd_qgemm(const void* packed_w, const float* scale, const uint16_t* a, int32_t B,
                    int32_t K, int32_t N, float* out, int32_t workgroups, void* workspace,
                    size_t workspace_bytes, void* stream);

@@ -99,9 +99,10 @@ def workspace_bytes(desc: ModelDesc, B: int, L_ctx: int) -> int:
     return n.value
 
 
-def qgemm_workspace_bytes(B: int, K: int, N: int) -> int:
+def qgemm_workspace_bytes(B: int, K: int, N: int, workgroups: int = 0) -> int:
     n = ctypes.c_size_t(0)
-    _check(lib().pd_qgemm_workspace_bytes(ctypes.c_int32(B), ctypes.c_int32(K), ctypes.c_int32(N), ctypes.byref(n)))
+    _check(lib().pd_qgemm_workspace_bytes(ctypes.c_int32(B), ctypes.c_int32(K), ctypes.c_int32(N),
+                                          ctypes.c_int32(workgroups), ctypes.byref(n)))
     return n.value
 
 

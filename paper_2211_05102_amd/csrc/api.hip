@@ -83,41 +83,65 @@ int auto_bps(int B, int L_ctx) {
     return (int)v;
 }
 
-// Launch plan of the two projections for batch B: workgroups (stream-K shares of the
-// weight matrix) and partial-sum slots per tile.  Fixed by the shape alone -- the
-// chip this library is written for has 256 compute units -- so results do not
-// depend on where the code runs and the workspace can be sized on the host.
-constexpr int PD_NUM_CUS = 256;
-struct GemmPlan {
-    int G_in, slots_in, G_out, slots_out;
+// Launch plans of the two projections for batch B: workgroups (stream-K shares of
+// the weight matrix), scale blocks of the operand, partial-sum slots per tile.
+// Fixed by the shape alone -- the chip this library is written for has 256 compute
+// units -- so results do not depend on where the code runs and the workspace can
+// be sized on the host.
+constexpr int PD_GEMM_WORKGROUPS = 256;
+struct GemmPlans {
+    pd::SkqPlan in, out;
+    int slots_in, slots_out;
+    int blk_o, blk_a;  // scale blocks (in 128-element chunks) of the attention and SwiGLU outputs
 };
-GemmPlan gemm_plan(const Shape& s, int B, int g_in_opt, int g_out_opt) {
-    GemmPlan p;
-    pd::qgemm_plan(B, s.d, s.n_in, g_in_opt > 0 ? g_in_opt : PD_NUM_CUS, &p.G_in, &p.slots_in);
-    pd::qgemm_plan(B, s.k_out, s.d, g_out_opt > 0 ? g_out_opt : PD_NUM_CUS, &p.G_out, &p.slots_out);
+GemmPlans gemm_plans(const Shape& s, int B, int g_in_opt, int g_out_opt) {
+    GemmPlans p;
+    // scale blocks of the projection operands (chunks that share one power-of-two
+    // scale): LayerNorm output = one scale per row; attention output and SwiGLU
+    // output = blocks of blk_o and blk_a chunks
+    const int c_in = s.d / 128, c_attn = s.H * s.dh / 128, c_ffn = s.F / 128;
+    const int blk_ln = c_in < 1024 ? c_in : 1024;
+    p.blk_o = c_attn < 16 ? c_attn : 16;
+    p.blk_a = c_ffn < 16 ? c_ffn : 16;
+    p.in = pd::qgemm_plan(B, s.d, s.n_in, g_in_opt > 0 ? g_in_opt : PD_GEMM_WORKGROUPS, 0, 1, blk_ln, &p.slots_in);
+    p.out = pd::qgemm_plan(B, s.k_out, s.d, g_out_opt > 0 ? g_out_opt : PD_GEMM_WORKGROUPS, c_attn, p.blk_o,
+                           p.blk_a, &p.slots_out);
     return p;
 }
 
-// workspace carving; sized for the largest slot counts so options never overflow it
+// Upper bound of the segments in one tile for ANY workgroup count up to the automatic
+// one: scale-block starts inside a tile, plus the workgroup range starts that can
+// fall into one tile, plus one.
+int slots_bound(pd::SkqPlan pl) {
+    pl.G = 1;
+    const int block_starts = pd::skq_segments_upto(0, pl.C - 1, pl);
+    return 1 + block_starts + PD_GEMM_WORKGROUPS / pl.T + 1;
+}
+
+// workspace carving; the partial-sum areas hold slots_bound() slots, so a workgroup
+// count set through pd_set_option never overflows them
 struct Workspace {
-    size_t flag, cs, xres, h, hs, part_in, q, act, acts, opart, ml, part_out, stats, total;
+    size_t flag, cs, xres, h, hs, part_in, nseg_in, q, act, acts, opart, ml, part_out, nseg_out, stats, total;
 };
 Workspace workspace_layout(const Shape& s, int B, int L_ctx) {
     Workspace w;
     size_t o = 0;
     const size_t nsplit_max = (size_t)(L_ctx / 32 + PD_MIN_BLOCKS_PER_SPLIT - 1) / PD_MIN_BLOCKS_PER_SPLIT;
+    const GemmPlans gp = gemm_plans(s, B, 0, 0);
     w.flag = o; o += 1024;  // 256 per-row position flags
     w.cs = o; o += align256((size_t)B * (s.dh / 2) * 2 * 4);
     w.xres = o; o += align256((size_t)B * s.d * 4);
     w.h = o; o += align256((size_t)B * s.d * 3);                    // digit planes of LN(x)
     w.hs = o; o += align256((size_t)(s.d / 128) * 256 * 4);         // their scales [chunk][256]
-    w.part_in = o; o += align256((size_t)PD_MAX_SPLITS * B * s.n_in * 4);  // slots <= PD_MAX_SPLITS
+    w.part_in = o; o += align256((size_t)slots_bound(gp.in) * gp.in.rows * s.n_in * 4);
+    w.nseg_in = o; o += align256((size_t)gp.in.T * 4);
     w.q = o; o += align256((size_t)B * s.H * s.dh * 4);
     w.act = o; o += align256((size_t)B * s.k_out * 3);              // digit planes of [o | a]
     w.acts = o; o += align256((size_t)(s.k_out / 128) * 256 * 4);
     w.opart = o; o += align256((size_t)B * nsplit_max * s.H * s.dh * 4);
     w.ml = o; o += align256((size_t)B * nsplit_max * s.H * 2 * 4);
-    w.part_out = o; o += align256((size_t)PD_MAX_SPLITS * B * s.d * 4);
+    w.part_out = o; o += align256((size_t)slots_bound(gp.out) * gp.out.rows * s.d * 4);
+    w.nseg_out = o; o += align256((size_t)gp.out.T * 4);
     w.stats = o; o += align256((size_t)B * ((s.d + 1023) / 1024) * 4 * 4);  // LayerNorm slice statistics
     w.total = o;
     return w;
@@ -195,21 +219,21 @@ pd_status run_layers(pd_handle* h, const StepArgs& a, hipStream_t st) {
     float* ml = reinterpret_cast<float*>(a.ws + w.ml);
     float* part_out = reinterpret_cast<float*>(a.ws + w.part_out);
 
-    const GemmPlan gp = gemm_plan(s, B, h->opt_g_in, h->opt_g_out);
-    const pd::SkqPlan pl_in = pd::qgemm_skq(B, s.d, s.n_in, gp.G_in);
-    const pd::SkqPlan pl_out = pd::qgemm_skq(B, s.k_out, s.d, gp.G_out);
-    // scale blocks of the projection operands (chunks of 128 that share one
-    // power-of-two scale): LayerNorm output = one scale per row; attention output
-    // and SwiGLU output = blocks of blk_o and blk_a chunks
-    const int c_in = s.d / 128, c_attn = s.H * s.dh / 128, c_ffn = s.F / 128;
-    const int blk_ln = c_in < 1024 ? c_in : 1024;
-    const int blk_o = c_attn < 16 ? c_attn : 16;
-    const int blk_a = c_ffn < 16 ? c_ffn : 16;
+    GemmPlans gp = gemm_plans(s, B, h->opt_g_in, h->opt_g_out);
+    gp.in.nseg = reinterpret_cast<const int*>(a.ws + w.nseg_in);
+    gp.out.nseg = reinterpret_cast<const int*>(a.ws + w.nseg_out);
+    if (gp.slots_in > slots_bound(gp.in) || gp.slots_out > slots_bound(gp.out))
+        return fail(PD_ERR_STATE, "internal: partial-sum slots exceed the workspace bound");
+    const pd::SkqPlan& pl_in = gp.in;
+    const pd::SkqPlan& pl_out = gp.out;
+    const int blk_o = gp.blk_o, blk_a = gp.blk_a;
     const int bps = h->opt_bps > 0 ? h->opt_bps : auto_bps(B, a.L_ctx);
     const int nd = h->act_digits;
     const size_t kv_layer_bytes = kv_layer_elems(s, B, a.L_ctx) * 2;
 
     PD_TRY_HIP(pd::launch_prep(a.positions, B, a.L_ctx, s.dh, h->desc.rope_base, cs, flag, st), "prep");
+    PD_TRY_HIP(pd::launch_skq_table(pl_in, reinterpret_cast<int*>(a.ws + w.nseg_in), st), "segment table (in)");
+    PD_TRY_HIP(pd::launch_skq_table(pl_out, reinterpret_cast<int*>(a.ws + w.nseg_out), st), "segment table (out)");
     for (int i = 0; i < a.n_run; i++) {
         const unsigned char* L = a.packed + (size_t)i * pl.total;
         const float* s_in = reinterpret_cast<const float*>(L + pl.s_in);
@@ -220,7 +244,7 @@ pd_status run_layers(pd_handle* h, const StepArgs& a, hipStream_t st) {
         if (i == 0)
             PD_TRY_HIP(pd::launch_ln_first(a.x_in, gamma, B, s.d, h->desc.ln_eps, xres, hq, hs, nd, st), "ln_first");
         prof_mark(h, PROF_QGEMM_IN, st);
-        PD_TRY_HIP(pd::launch_qgemm(L + pl.w_in, hq, hs, part_in, B, s.d, s.n_in, gp.G_in, 0, 1, blk_ln, nd, st), "qgemm_in");
+        PD_TRY_HIP(pd::launch_qgemm(L + pl.w_in, hq, hs, part_in, B, s.d, s.n_in, pl_in, nd, st), "qgemm_in");
         prof_mark(h, PROF_QGEMM_IN, st);
         prof_mark(h, PROF_EPI_IN, st);
         PD_TRY_HIP(pd::launch_epi_in(part_in, pl_in, s_in, cs, a.positions, B, s.H, s.dh, s.F, a.L_ctx, q,
@@ -231,8 +255,7 @@ pd_status run_layers(pd_handle* h, const StepArgs& a, hipStream_t st) {
                                          nullptr, actq, acts, s.k_out, blk_o, nd, st), "mqa_attend");
         prof_mark(h, PROF_ATTEND, st);
         prof_mark(h, PROF_QGEMM_OUT, st);
-        PD_TRY_HIP(pd::launch_qgemm(L + pl.w_out, actq, acts, part_out, B, s.k_out, s.d, gp.G_out, c_attn, blk_o,
-                                    blk_a, nd, st), "qgemm_out");
+        PD_TRY_HIP(pd::launch_qgemm(L + pl.w_out, actq, acts, part_out, B, s.k_out, s.d, pl_out, nd, st), "qgemm_out");
         prof_mark(h, PROF_QGEMM_OUT, st);
         const bool last = i == a.n_run - 1;
         prof_mark(h, PROF_EPI_OUT, st);
@@ -348,7 +371,7 @@ pd_status pd_destroy(pd_handle* h) {
 pd_status pd_set_option(pd_handle* h, const char* name, int32_t value) {
     if (!h || !name) return fail(PD_ERR_NULL, "NULL argument");
     if (!strcmp(name, "gemm_workgroups_in") || !strcmp(name, "gemm_workgroups_out")) {
-        if (value < 0 || value > 4096) return fail(PD_ERR_RANGE, "workgroup count must be in 0..4096");
+        if (value < 0 || value > PD_GEMM_WORKGROUPS) return fail(PD_ERR_RANGE, "workgroup count must be in 0..256");
         (!strcmp(name, "gemm_workgroups_in") ? h->opt_g_in : h->opt_g_out) = value;
         return PD_OK;
     }
@@ -478,11 +501,31 @@ pd_status pd_check_async(pd_handle* h, void* workspace, void* stream) {
     return PD_OK;
 }
 
-pd_status pd_qgemm_workspace_bytes(int32_t B, int32_t K, int32_t N, size_t* bytes) {
+namespace {
+// test entry: every 128-element chunk has its own scale (blocks of one chunk)
+struct QgemmWs {
+    pd::SkqPlan pl;
+    size_t part, qa, qs, nseg, total;
+};
+QgemmWs qgemm_ws(int B, int K, int N, int workgroups) {
+    QgemmWs q;
+    int slots = 1;
+    q.pl = pd::qgemm_plan(B, K, N, workgroups > 0 ? workgroups : PD_GEMM_WORKGROUPS, 0, 1, 1, &slots);
+    size_t o = 0;
+    q.part = o; o += align256((size_t)slots * q.pl.rows * N * 4);
+    q.qa = o; o += align256((size_t)B * K * 3);
+    q.qs = o; o += align256((size_t)(K / 128) * 256 * 4);
+    q.nseg = o; o += align256((size_t)q.pl.T * 4);
+    q.total = o;
+    return q;
+}
+}  // namespace
+
+pd_status pd_qgemm_workspace_bytes(int32_t B, int32_t K, int32_t N, int32_t workgroups, size_t* bytes) {
     if (!bytes) return fail(PD_ERR_NULL, "bytes is NULL");
     if (B < 1 || B > 256 || K < 128 || K % 128 || N < 32 || N % 32) return fail(PD_ERR_SHAPE, "unsupported GEMM shape");
-    *bytes = align256((size_t)PD_MAX_SPLITS * B * N * 4) + align256((size_t)B * K * 3) +
-             align256((size_t)(K / 128) * 256 * 4);
+    if (workgroups < 0 || workgroups > 4096) return fail(PD_ERR_RANGE, "workgroups out of range");
+    *bytes = qgemm_ws(B, K, N, workgroups).total;
     return PD_OK;
 }
 
@@ -491,23 +534,22 @@ pd_status pd_qgemm(const void* packed_w, const float* scale, const uint16_t* a, 
                    void* stream) {
     if (!packed_w || !scale || !a || !out || !workspace) return fail(PD_ERR_NULL, "NULL device pointer");
     size_t need = 0;
-    pd_status rc = pd_qgemm_workspace_bytes(B, K, N, &need);
+    pd_status rc = pd_qgemm_workspace_bytes(B, K, N, workgroups, &need);
     if (rc != PD_OK) return rc;
     if (workspace_bytes < need) return fail(PD_ERR_WORKSPACE, "workspace too small");
     if (!aligned(packed_w, 256) || !aligned(workspace, 256) || !aligned(a, 16) || !aligned(out, 16))
         return fail(PD_ERR_ALIGN, "misaligned device pointer");
-    if (workgroups < 0 || workgroups > 4096) return fail(PD_ERR_RANGE, "workgroups out of range");
-    int G = 0, slots = 0;
-    pd::qgemm_plan(B, K, N, workgroups > 0 ? workgroups : PD_NUM_CUS, &G, &slots);
+    QgemmWs q = qgemm_ws(B, K, N, workgroups);
     hipStream_t st = static_cast<hipStream_t>(stream);
     unsigned char* wsb = static_cast<unsigned char*>(workspace);
-    float* part = reinterpret_cast<float*>(wsb);
-    unsigned char* qa = wsb + align256((size_t)PD_MAX_SPLITS * B * N * 4);
-    float* qs = reinterpret_cast<float*>(qa + align256((size_t)B * K * 3));
-    PD_TRY_HIP(pd::launch_quantize_bf16(a, qa, qs, B, K, 3, st), "quantize");
-    // the test quantiser gives every 128-element chunk its own scale: blocks of one chunk
-    PD_TRY_HIP(pd::launch_qgemm(packed_w, qa, qs, part, B, K, N, G, 0, 1, 1, 3, st), "qgemm");
-    PD_TRY_HIP(pd::launch_qgemm_reduce(part, scale, out, B, K, N, G, st), "qgemm_reduce");
+    float* part = reinterpret_cast<float*>(wsb + q.part);
+    float* qs = reinterpret_cast<float*>(wsb + q.qs);
+    int* nseg = reinterpret_cast<int*>(wsb + q.nseg);
+    q.pl.nseg = nseg;
+    PD_TRY_HIP(pd::launch_skq_table(q.pl, nseg, st), "segment table");
+    PD_TRY_HIP(pd::launch_quantize_bf16(a, wsb + q.qa, qs, B, K, 3, st), "quantize");
+    PD_TRY_HIP(pd::launch_qgemm(packed_w, wsb + q.qa, qs, part, B, K, N, q.pl, 3, st), "qgemm");
+    PD_TRY_HIP(pd::launch_qgemm_reduce(part, scale, out, B, N, q.pl, st), "qgemm_reduce");
     return PD_OK;
 }
 

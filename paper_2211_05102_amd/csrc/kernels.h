@@ -5,26 +5,25 @@
 
 #include "common.h"
 
-#define PD_MAX_SPLITS 16          // K-splits of a projection
 #define PD_MIN_BLOCKS_PER_SPLIT 4 // 32-token blocks per attention workgroup, lower bound
 
 namespace pd {
 
 // ---- qgemm.hip
 void qgemm_config(int B, int* bm, int* ns, int* tile_cols);
-void qgemm_plan(int B, int K, int N, int num_cus, int* G, int* slots);
-SkqPlan qgemm_skq(int B, int K, int N, int G);
+SkqPlan qgemm_plan(int B, int K, int N, int workgroups, int c_split, int blk0, int blk1,
+                   int* max_slots);
+hipError_t launch_skq_table(SkqPlan pl, int* nseg, hipStream_t stream);
 hipError_t launch_qgemm(const void* wp, const void* qa, const float* scale_t, float* part, int B,
-                        int K, int N, int G, int c_split, int blk0, int blk1, int nd,
-                        hipStream_t stream);
+                        int K, int N, SkqPlan pl, int nd, hipStream_t stream);
 hipError_t launch_quantize_bf16(const uint16_t* a, void* qa, float* scale_t, int B, int K, int nd,
                                 hipStream_t stream);
 hipError_t launch_pack_matrix(const int8_t* w, void* dst, int K, int N, int mode, int n_qkv, int F,
                               hipStream_t stream);
 hipError_t launch_pack_vector(const uint16_t* src, float* dst, int N, int mode, int n_qkv, int F,
                               hipStream_t stream);
-hipError_t launch_qgemm_reduce(const float* part, const float* scale, float* out, int B, int K,
-                               int N, int G, hipStream_t stream);
+hipError_t launch_qgemm_reduce(const float* part, const float* scale, float* out, int B, int N,
+                               SkqPlan pl, hipStream_t stream);
 
 // ---- attention.hip
 hipError_t launch_mqa_attend(const float* q, const void* kc_layer, const void* vc_layer,

@@ -90,7 +90,7 @@ __global__ __launch_bounds__(256) void ln_first_kernel(const uint16_t* __restric
 // sum over the partial slots of the tile that holds packed column `col` (fixed order)
 __device__ __forceinline__ float sum_partials(const float* __restrict__ part, const SkqPlan& pl,
                                               size_t stride, size_t off, int col) {
-    const int ns = skq_slots(col / pl.tile_cols, pl.C, pl.T, pl.G);
+    const int ns = pl.nseg[col / pl.tile_cols];
     float acc = 0.f;
     for (int s = 0; s < ns; s++) acc += part[(size_t)s * stride + off];
     return acc;
@@ -116,7 +116,7 @@ __global__ __launch_bounds__(256) void epi_in_kernel(
     const int n_qkv = H * dh + 2 * dh;
     const int N = n_qkv + 2 * F;
     const int k_out = H * dh + F;
-    const size_t stride = (size_t)B * N, rowoff = (size_t)b * N;
+    const size_t stride = (size_t)pl.rows * N, rowoff = (size_t)b * N;
 
     if ((int)blockIdx.x >= n_blocks_a) {
         const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -130,7 +130,7 @@ __global__ __launch_bounds__(256) void epi_in_kernel(
             if (j < c_hi) {
                 const int f = j * QCHUNK + 2 * lane;  // f and f + 1 share a 32-group
                 const int pcol = n_qkv + (f >> 5) * 64 + (f & 31);
-                const int ns = skq_slots(pcol / pl.tile_cols, pl.C, pl.T, pl.G);
+                const int ns = pl.nseg[pcol / pl.tile_cols];
                 float g0 = 0.f, g1 = 0.f, u0 = 0.f, u1 = 0.f;
                 for (int s = 0; s < ns; s++) {  // fixed order
                     const float* p = part + (size_t)s * stride + rowoff + pcol;
@@ -212,10 +212,10 @@ __global__ __launch_bounds__(256) void residual_kernel(const float* __restrict__
     __shared__ float red[4];
     const int tid = threadIdx.x, b = blockIdx.y, c = (blockIdx.x * 256 + tid) * 4;
     const bool in = c < d;
-    const size_t stride = (size_t)B * d, off = (size_t)b * d + c;
+    const size_t stride = (size_t)pl.rows * d, off = (size_t)b * d + c;
     f32x4 xn = {0.f, 0.f, 0.f, 0.f};
     if (in) {
-        const int ns = skq_slots(c / pl.tile_cols, pl.C, pl.T, pl.G);  // 4 columns share a tile
+        const int ns = pl.nseg[c / pl.tile_cols];  // 4 columns share a tile
         f32x4 acc = {0.f, 0.f, 0.f, 0.f};
         for (int s = 0; s < ns; s++) acc += *reinterpret_cast<const f32x4*>(part + (size_t)s * stride + off);
         const f32x4 sc = *reinterpret_cast<const f32x4*>(scale + c);

@@ -32,6 +32,8 @@
 // bytes (+-1 unit), whatever the matrix shape.  A tile covered by several
 // workgroups gets one partial per workgroup, in slot (g - first g of the tile);
 // consumers add the slots in index order, so results do not depend on timing.
+#include <stdlib.h>
+
 #include "common.h"
 #include "kernels.h"
 
@@ -44,26 +46,35 @@ __device__ __forceinline__ void lds_barrier() {
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
+constexpr int NT = 256;  // threads per GEMM workgroup: 4 waves, one per SIMD, 512 registers each
+
+#ifdef PD_DBG_TIMING /* tuning experiment: per-phase cycle counts of wave 0 of each workgroup */
+__device__ long long pd_dbg[4096 * 8];
+#define PD_T(x) const long long x = clock64();
+#define PD_TACC(a, x, y) a += (y) - (x);
+#else
+#define PD_T(x)
+#define PD_TACC(a, x, y)
+#endif
+
 // BM: 32-row batch blocks held in accumulators; NS: 32-column subtiles per wave;
-// R: weight units per wave held in a register ring (R - 1 in flight while one is
-// consumed).  grid = (G workgroups, row groups of 32*BM rows).
+// R: weight units per wave held in a register ring.  grid = (G workgroups, row
+// groups of 32*BM rows).  Two workgroups share a compute unit (256 VGPRs per
+// wave, under 80 KiB of LDS each): every step ends in a workgroup barrier, and
+// it is the other workgroup's MFMAs that fill the matrix pipe while one waits.
 //
-// Weights go HBM -> registers with non-temporal 16-byte loads (each is 1 KiB
+// Weights go HBM -> registers with non-temporal buffer loads (each is 1 KiB
 // contiguous per wave and already a B operand); the loop body is unrolled R
 // times so every ring slot is a fixed register range and the compiler's own
-// vmcnt bookkeeping keeps exactly R - 1 units in flight.  Every step issues the
-// same loads unconditionally (past the end of the range the last unit is
-// fetched again, an L2 hit) so that no control-flow join weakens those waits.
-// Activations of the next unit travel L2 -> registers -> LDS behind the MFMAs
-// of the current one and are shared by the 4 waves.
-constexpr int NT = 512;  // threads per GEMM workgroup (8 waves, two per SIMD)
-
-template <int BM, int NS, int ND, int R>
+// vmcnt bookkeeping keeps the ring in flight.  Every step issues the same loads
+// unconditionally (past the end of the range the last unit is fetched again,
+// an L2 hit) so that no control-flow join weakens those waits.
+template <int BM, int NS, int ND, int R, int AD>
 __global__ __launch_bounds__(NT) void qgemm_kernel(const uint4* __restrict__ wp,
-                                                    const unsigned char* __restrict__ qa,
-                                                    const float* __restrict__ scale_t,
-                                                    float* __restrict__ part, int B, int K, int N,
-                                                    int c_split, int blk0, int blk1) {
+                                                      const unsigned char* __restrict__ qa,
+                                                      const float* __restrict__ scale_t,
+                                                      float* __restrict__ part, int B, int K, int N,
+                                                      SkqPlan pl) {
     constexpr int KC = QCHUNK;                  // k-extent of one unit = one LDS stage
     constexpr int ROWS = BM * 32;
     constexpr int PITCH = ND * KC + 16;         // bytes; +16 spreads rows over LDS banks
@@ -72,27 +83,30 @@ __global__ __launch_bounds__(NT) void qgemm_kernel(const uint4* __restrict__ wp,
     constexpr int KB = KC / 32;                 // 32-k blocks per unit
     constexpr int TSUB = (NT / 64) * NS;        // 32-column subtiles per tile
     constexpr int STAGE = ROWS * PITCH + ROWS * 4;  // digits + one scale per row
-    static_assert(R == 2 || R == 4 || R == 6, "ring depth (even: the activation register stages alternate)");
-    __shared__ __attribute__((aligned(16))) unsigned char lds[2][STAGE];
-    // fp32 tile accumulator, one private column per thread: it is touched only when
-    // a scale block or a tile ends, so it lives in LDS and leaves the registers to
-    // the int32 accumulators and the weight ring
-    __shared__ float accl[NS * BM * 16][NT];
+    static_assert(3 + APT < KB * ND, "stage write fits behind the loads in one unit");
+    static_assert(R == 2 || R == 4, "ring depth (even: the activation register stages alternate with the ring slots)");
+    static_assert(3 * STAGE <= 160 * 1024, "LDS");
+    __shared__ __attribute__((aligned(16))) unsigned char lds[3][STAGE];
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform: lets addresses stay scalar
     const int g = lane >> 5, l32 = lane & 31;
     const int n_sub = N >> 5;
-    const int kblocks = K >> 5;
-    const int C = K >> 7;                                   // chunks per tile
-    const int T = (n_sub + TSUB - 1) / TSUB;                // tiles
+    const int C = pl.C, T = pl.T, G = pl.G;
+    const int c_split = pl.c_split, blk0 = pl.blk0, blk1 = pl.blk1;
     const long long U = (long long)T * C;
-    const int G = gridDim.x;
-    const long long u0 = (long long)blockIdx.x * U / G, u1 = ((long long)blockIdx.x + 1) * U / G;
+    // (32-bit from here on: the launcher rejects U >= 2^31, and 64-bit compares would run on the vector ALU)
+    // Integer division runs on the vector ALU and leaves its (uniform) result in a
+    // vector register; readfirstlane moves it to a scalar one so that everything
+    // derived from it -- unit counters, buffer offsets, loop exits -- stays scalar.
+    const int u0 = __builtin_amdgcn_readfirstlane((int)skq_begin(blockIdx.x, U, G, pl.align));
+    const int u1 = __builtin_amdgcn_readfirstlane((int)skq_begin(blockIdx.x + 1, U, G, pl.align));
     if (u0 >= u1) return;
     const int row0 = blockIdx.y * ROWS;
 
     // byte offsets (within one chunk column of the activation matrix) of the pieces
-    // this thread moves; rows >= B repeat row B-1 (their results are never stored)
+    // this thread moves, and where they go in an LDS stage; rows >= B repeat row B-1
+    // (their results are never stored)
     uint32_t aoff[APT], aslot[APT];
 #pragma unroll
     for (int it = 0; it < APT; it++) {
@@ -103,35 +117,63 @@ __global__ __launch_bounds__(NT) void qgemm_kernel(const uint4* __restrict__ wp,
         rg = rg < B ? rg : B - 1;
         aoff[it] = (uint32_t)rg * (uint32_t)(K * ND) + (p_ % PPR) * 16;
     }
-    int srow = row0 + tid;
+    // (every thread moves a row scale: threads beyond the rows repeat the first ones)
+    int srow = row0 + (tid & (ROWS - 1));
     srow = srow < B ? srow : B - 1;
+    const uint32_t srow4 = srow * 4, sslot = ROWS * PITCH + (tid & (ROWS - 1)) * 4;
+    // Every global read is a buffer load: a scalar descriptor and a scalar byte
+    // offset that moves with the unit, plus a per-lane offset that never changes --
+    // no 64-bit address arithmetic in vector registers, and reads past the end of
+    // a range return zero instead of faulting.
+    const uint32_t lane16 = lane * 16;
+    const __amdgpu_buffer_rsrc_t a_rs = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<unsigned char*>(qa), 0, B * K * ND, 0x00020000);
+    const __amdgpu_buffer_rsrc_t s_rs = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float*>(scale_t), 0, C * QSCALE_ROWS * 4, 0x00020000);
+    // partial sums: slots of pl.rows (whole row groups) x N, so stores need no row test
+    const __amdgpu_buffer_rsrc_t p_rs = __builtin_amdgcn_make_buffer_rsrc(
+        part, 0, (int)((uint32_t)pl.max_slots * (uint32_t)pl.rows * (uint32_t)N * 4u), 0x00020000);
+    // One descriptor spans the whole packed matrix; the 32-column stream of subtile i
+    // and the unit inside it are a scalar byte offset that advances by one unit per
+    // step (a constant) and is recomputed only when the fetch moves to the next tile.
+    const __amdgpu_buffer_rsrc_t w_rs = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<unsigned char*>(reinterpret_cast<const unsigned char*>(wp)), 0,
+        (int)((uint32_t)n_sub * (uint32_t)K * 32u), 0x00020000);
+    uint32_t w_so[NS];
+#pragma unroll
+    for (int i = 0; i < NS; i++) w_so[i] = 0;
+    uint32_t a_so = 0, s_so = 0;  // byte offsets of chunk c_a in the activation and scale arrays
 
+    // The int32 accumulators live in the accumulation registers (AGPRs) for the whole
+    // loop.  They are cleared by an MFMA of zeros rather than by moves: the register
+    // allocator keeps a loop-carried tile in AGPRs only if every value that flows into
+    // it comes out of an MFMA; a single VALU-written zero makes it hold the tiles in
+    // VGPRs and copy all of them to and from AGPRs around every unit.
+    const i32x4 zero4 = {0, 0, 0, 0};
+    const i32x16 zero16 = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
     i32x16 iacc[ND][NS][BM];
 #pragma unroll
-    for (int i = 0; i < NS; i++)
+    for (int p = 0; p < ND; p++)
 #pragma unroll
-        for (int bm = 0; bm < BM; bm++) {
+        for (int i = 0; i < NS; i++)
 #pragma unroll
-            for (int r = 0; r < 16; r++) accl[(i * BM + bm) * 16 + r][tid] = 0.f;
-#pragma unroll
-            for (int p = 0; p < ND; p++)
-#pragma unroll
-                for (int r = 0; r < 16; r++) iacc[p][i][bm][r] = 0;
-        }
+            for (int bm = 0; bm < BM; bm++)
+                iacc[p][i][bm] = __builtin_amdgcn_mfma_i32_32x32x32_i8(zero4, zero4, zero16, 0, 0, 0);
 
-    uint4 wreg[R][NS][KB];
-    const uint4* wsrc[NS];
+    u32x4 wreg[R][NS][KB];
     u32x4 areg[2][APT];
     float sreg[2] = {0.f, 0.f};
+    i32x4 aop[AD][BM];  // operand reads run AD - 1 groups ahead of their MFMAs
 
     // (tile, chunk) of the unit being computed; of the next weight unit to fetch
     // (saturates at the last unit of the range); chunk of the next activation stage
-    int t_cur = (int)(u0 / C), c_cur = (int)(u0 % C);
+    int t_cur = __builtin_amdgcn_readfirstlane(u0 / C);
+    int c_cur = u0 - t_cur * C;
     int t_w = t_cur, c_w = c_cur, c_a = c_cur;
-    long long u = u0, u_w = u0, u_a = u0;
+    int u = u0, u_w = u0, u_a = u0;
+    int slot = __builtin_amdgcn_readfirstlane(skq_segments_upto(t_cur, c_cur, pl));  // partial slot of the segment being accumulated
 
-    // end of the scale block that holds chunk c: chunks [0, c_split) come in blocks
-    // of blk0, chunks [c_split, C) in blocks of blk1
+    // end of the scale block that holds chunk c
     auto block_end = [&](int c) {
         int e;
         if (c < c_split) {
@@ -141,7 +183,7 @@ __global__ __launch_bounds__(NT) void qgemm_kernel(const uint4* __restrict__ wp,
             e = c_split + ((c - c_split) / blk1 + 1) * blk1;
             e = e < C ? e : C;
         }
-        return e;
+        return __builtin_amdgcn_readfirstlane(e);
     };
     int seg_end = block_end(c_cur);
 
@@ -150,189 +192,305 @@ __global__ __launch_bounds__(NT) void qgemm_kernel(const uint4* __restrict__ wp,
     _Pragma("unroll") for (int i = 0; i < NS; i++) {                                     \
         int st_ = t_w * TSUB + wave * NS + i;                                            \
         st_ = st_ < n_sub ? st_ : n_sub - 1; /* ragged last tile: result dropped */      \
-        wsrc[i] = wp + ((size_t)st_ * kblocks + (size_t)c_w * KB) * 64 + lane;           \
+        w_so[i] = (uint32_t)st_ * (uint32_t)(K * 32) + (uint32_t)c_w * (KC * 32);        \
     }
+    // non-temporal: each weight byte is read once per step
 #define PD_W_LOAD(s, kb)                                                                 \
-    _Pragma("unroll") for (int i = 0; i < NS; i++) wreg[s][i][kb] = ld_stream(wsrc[i] + (kb) * 64);
+    _Pragma("unroll") for (int i = 0; i < NS; i++)                                       \
+        wreg[s][i][kb] = __builtin_amdgcn_raw_buffer_load_b128(w_rs, lane16 + (kb) * 1024, w_so[i], 2);
+#define PD_W_REFILL(s, kb) PD_W_LOAD(s, kb)
+    // (past the end of the range the last unit is fetched again: an L2 hit; selects
+    // rather than branches, except for the rare move to the next tile)
 #define PD_W_NEXT()                                                                      \
-    if (u_w + 1 < u1) {                                                                  \
-        u_w++;                                                                           \
-        if (++c_w == C) { c_w = 0; t_w++; }                                              \
+    {                                                                                    \
+        const int nu_ = u_w + 1 < u1 - 1 ? u_w + 1 : u1 - 1; /* s_min: no compare result to widen */ \
+        const int adv_ = nu_ - u_w;                                                      \
+        u_w = nu_;                                                                       \
+        c_w += adv_;                                                                     \
+        if (c_w == C) {                                                                  \
+            c_w = 0;                                                                     \
+            t_w++;                                                                       \
+            PD_W_PTRS()                                                                  \
+        } else {                                                                         \
+            _Pragma("unroll") for (int i = 0; i < NS; i++) w_so[i] += adv_ * (KC * 32);  \
+        }                                                                                \
     }
 #define PD_FETCH_W(s)                                                                    \
     {                                                                                    \
-        PD_W_PTRS()                                                                      \
         _Pragma("unroll") for (int kb = 0; kb < KB; kb++) { PD_W_LOAD(s, kb) }           \
         PD_W_NEXT()                                                                      \
     }
-    // activations of the unit two steps ahead -> register stage `as`; vector-memory
-    // operations retire in order, so a load that is waited on must be older than
-    // everything that is meant to stay in flight: these loads are consumed one step
-    // after they are issued, with R - 1 weight units still outstanding behind them
+#define PD_A_NEXT()                                                                      \
+    {                                                                                    \
+        const int nu_ = u_a + 1 < u1 - 1 ? u_a + 1 : u1 - 1;                             \
+        const int adv_ = nu_ - u_a;                                                      \
+        u_a = nu_;                                                                       \
+        c_a += adv_;                                                                     \
+        a_so += adv_ * (ND * KC);                                                        \
+        s_so += adv_ * (QSCALE_ROWS * 4);                                                \
+        const bool wrap_ = c_a == C;                                                     \
+        c_a = wrap_ ? 0 : c_a;                                                           \
+        a_so = wrap_ ? 0 : a_so;                                                         \
+        s_so = wrap_ ? 0 : s_so;                                                         \
+    }
+    // activations (and row scales) of chunk c_a -> register stage `as`
+#define PD_A_NOW(as)                                                                     \
+    {                                                                                    \
+        _Pragma("unroll") for (int it = 0; it < APT; it++)                               \
+            areg[as][it] = __builtin_amdgcn_raw_buffer_load_b128(a_rs, aoff[it], a_so, 0); \
+        sreg[as] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(       \
+            s_rs, srow4, s_so, 0));                                                      \
+    }
+    // ... of the next unit not yet fetched.  Vector-memory operations retire in
+    // order, so a load that is waited on must be older than everything that is meant
+    // to stay in flight: these registers are written to LDS one step after the loads
+    // are issued, with weight units still outstanding behind them, and the LDS stage
+    // is read one step after that.
 #define PD_LOAD_A(as)                                                                    \
     {                                                                                    \
-        if (u_a + 1 < u1) {                                                              \
-            u_a++;                                                                       \
-            if (++c_a == C) c_a = 0;                                                     \
-        }                                                                                \
-        const unsigned char* base_ = qa + (size_t)c_a * (ND * KC);                       \
-        _Pragma("unroll") for (int it = 0; it < APT; it++)                               \
-            areg[as][it] = *reinterpret_cast<const u32x4*>(base_ + aoff[it]);            \
-        if (tid < ROWS) sreg[as] = scale_t[(size_t)c_a * QSCALE_ROWS + srow];            \
+        PD_A_NEXT()                                                                      \
+        PD_A_NOW(as)                                                                     \
     }
 #define PD_STORE_A(buf, as)                                                              \
     {                                                                                    \
         _Pragma("unroll") for (int it = 0; it < APT; it++)                               \
-            *reinterpret_cast<u32x4*>(&lds[buf][aslot[it]]) = areg[as][it];              \
-        if (tid < ROWS) *reinterpret_cast<float*>(&lds[buf][ROWS * PITCH + tid * 4]) = sreg[as]; \
+            *reinterpret_cast<u32x4*>(&ldsb[(buf) + aslot[it]]) = areg[as][it];              \
+        *reinterpret_cast<float*>(&ldsb[(buf) + sslot]) = sreg[as];                          \
     }
     // One unit of MFMAs.  Group gi = (kb, plane p): BM operand reads from LDS feed
-    // NS*BM MFMAs; the reads run two groups ahead of the MFMAs, and scheduling
-    // barriers keep that order (left alone, the scheduler hoists every read of the
-    // unit and runs out of registers).  As soon as the last plane of a 32-k block
-    // is issued, the ring registers of that block are refilled from the next unit.
-    // Plane 0 of a row chunk is the most significant digit.
-#define PD_A_READ(buf, gi, slot)                                                         \
+    // NS*BM MFMAs; the reads run two groups ahead of the MFMAs (those of groups 0
+    // and 1 were issued by the previous step, ahead of the workgroup barrier), and
+    // scheduling barriers keep that order (left alone, the scheduler hoists every
+    // read of the unit and runs out of registers).  As soon as the last plane of a
+    // 32-k block is issued, the ring registers of that block are refilled from the
+    // next unit.  Plane 0 of a row chunk is the most significant digit.
+#define PD_A_READ(buf, gi, slot_)                                                        \
     _Pragma("unroll") for (int bm = 0; bm < BM; bm++)                                    \
-        aop[slot][bm] = *reinterpret_cast<const i32x4*>(                                 \
-            &lds[buf][(bm * 32 + l32) * PITCH + ((gi) % ND) * KC + ((gi) / ND) * 32 + g * 16]);
-#define PD_MFMA(buf, s)                                                                  \
+        aop[slot_][bm] = *reinterpret_cast<const i32x4*>(                                \
+            &ldsb[(buf) + (bm * 32 + l32) * PITCH + ((gi) % ND) * KC + ((gi) / ND) * 32 + g * 16]);
+#define PD_MFMA1(gi, s, i, bm)                                                           \
+    iacc[(gi) % ND][i][bm] = __builtin_amdgcn_mfma_i32_32x32x32_i8(                      \
+        aop[(gi) % AD][bm], __builtin_bit_cast(i32x4, wreg[s][i][(gi) / ND]),            \
+        iacc[(gi) % ND][i][bm], 0, 0, 0);                                                \
+    __builtin_amdgcn_sched_barrier(0);
+#define PD_MFMA(buf, s, wbuf, as_load, as_store)                                         \
     {                                                                                    \
-        i32x4 aop[3][BM];                                                                \
-        PD_W_PTRS()                                                                      \
-        PD_A_READ(buf, 0, 0)                                                             \
-        PD_A_READ(buf, 1, 1)                                                             \
+        PD_A_NEXT()                                                                      \
         _Pragma("unroll") for (int gi = 0; gi < KB * ND; gi++) {                         \
-            if (gi + 2 < KB * ND) { PD_A_READ(buf, gi + 2, (gi + 2) % 3) }               \
-            _Pragma("unroll") for (int i = 0; i < NS; i++)                               \
-                _Pragma("unroll") for (int bm = 0; bm < BM; bm++)                        \
-                    iacc[gi % ND][i][bm] = __builtin_amdgcn_mfma_i32_32x32x32_i8(        \
-                        aop[gi % 3][bm], __builtin_bit_cast(i32x4, wreg[s][i][gi / ND]), \
-                        iacc[gi % ND][i][bm], 0, 0, 0);                                  \
-            if (gi % ND == ND - 1) { PD_W_LOAD(s, gi / ND) }                             \
+            /* One wave per SIMD: whatever is not an MFMA has to be issued while an   */ \
+            /* MFMA executes, so the other work of the group is spread between its    */ \
+            /* MFMAs and pinned there.                                                 */ \
+            PD_MFMA1(gi, s, 0, 0)                                                        \
+            if (gi + AD - 1 < KB * ND) { PD_A_READ(buf, gi + AD - 1, (gi + AD - 1) % AD) } \
+            __builtin_amdgcn_sched_barrier(0);                                           \
+            if (BM > 1) { PD_MFMA1(gi, s, 0, BM - 1) }                                   \
+            /* in the first three groups the loads of the activations three units     */ \
+            /* ahead (ahead of this step's weight loads in the queue, see PD_A_NOW),  */ \
+            /* then one piece per group of the stage write of the unit two ahead      */ \
+            if (gi < 3) {                                                                \
+                _Pragma("unroll") for (int it = 0; it < APT; it++)                       \
+                    if (it * 3 / APT == gi)                                              \
+                        areg[as_load][it] = __builtin_amdgcn_raw_buffer_load_b128(       \
+                            a_rs, aoff[it], a_so, 0);                                    \
+                if (gi == 2)                                                             \
+                    sreg[as_load] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32( \
+                        s_rs, srow4, s_so, 0));                                          \
+            } else if (gi - 3 < APT) {                                                   \
+                *reinterpret_cast<u32x4*>(&ldsb[(wbuf) + aslot[gi - 3]]) = areg[as_store][gi - 3]; \
+            } else if (gi - 3 == APT) {                                                  \
+                *reinterpret_cast<float*>(&ldsb[(wbuf) + sslot]) = sreg[as_store];           \
+            }                                                                            \
+            __builtin_amdgcn_sched_barrier(0);                                           \
+            if (NS > 1) {                                                                \
+                PD_MFMA1(gi, s, NS - 1, 0)                                               \
+                if (BM > 1) { PD_MFMA1(gi, s, NS - 1, BM - 1) }                          \
+            }                                                                            \
+            if (gi % ND == ND - 1) { PD_W_REFILL(s, gi / ND) }                           \
             __builtin_amdgcn_sched_barrier(0);                                           \
         }                                                                                \
         PD_W_NEXT()                                                                      \
     }
-    // acc += scale * sum_p 256^(ND-1-p) * float(iacc[p]); iacc = 0.  int32 bound per
-    // plane and scale block: 128 * 127 * 128 * chunks < 2^31 for blocks of up to 1023
-    // chunks.  Lane (l32, g) holds rows 8q + 4g + 0..3 of each 32-row block.
-#define PD_FOLD(buf)                                                                     \
-    _Pragma("unroll") for (int bm = 0; bm < BM; bm++) {                                  \
-        f32x4 sc[4];                                                                     \
-        _Pragma("unroll") for (int q = 0; q < 4; q++)                                    \
-            sc[q] = *reinterpret_cast<const f32x4*>(                                     \
-                &lds[buf][ROWS * PITCH + (bm * 32 + 8 * q + 4 * g) * 4]);                \
-        _Pragma("unroll") for (int i = 0; i < NS; i++) {                                 \
-            _Pragma("unroll") for (int r = 0; r < 16; r++) {                             \
-                float v_ = (float)iacc[0][i][bm][r];                                     \
-                _Pragma("unroll") for (int p = 1; p < ND; p++)                           \
-                    v_ = v_ * 256.0f + (float)iacc[p][i][bm][r];                         \
-                accl[(i * BM + bm) * 16 + r][tid] += sc[r >> 2][r & 3] * v_;             \
-                _Pragma("unroll") for (int p = 0; p < ND; p++) iacc[p][i][bm][r] = 0;    \
-            }                                                                            \
-            __builtin_amdgcn_sched_barrier(0); /* one tile at a time: bounded live set */ \
-        }                                                                                \
-    }
-    // D layout of the 32x32 MFMA: register r of lane (l32, g) is row 8*(r/4) + 4*g + r%4, column l32
-#define PD_STORE_TILE()                                                                  \
+    // A segment ends: part[slot] = scale * sum_p 256^(ND-1-p) * float(iacc[p]).
+    // int32 bound per plane and scale block: 128 * 127 * 128 * chunks < 2^31 for blocks
+    // of up to 1024 chunks.  D layout of the 32x32 MFMA: register r of lane (l32, g)
+    // is row 8*(r/4) + 4*g + r%4, column l32.
+    // (`opq` is a zero the compiler cannot see through: everything the stores need is
+    // computed from it, here, instead of being hoisted above the unit loop and kept in
+    // registers across it.)
+#define PD_CLOSE_SEGMENT(buf)                                                            \
     {                                                                                    \
-        const int slot_ = (int)blockIdx.x - skq_owner((long long)t_cur * C, U, G);       \
-        _Pragma("unroll") for (int i = 0; i < NS; i++) {                                 \
-            const int st_ = t_cur * TSUB + wave * NS + i;                                \
-            if (st_ < n_sub) {                                                           \
-                const int n_ = st_ * 32 + l32;                                           \
-                _Pragma("unroll") for (int bm = 0; bm < BM; bm++) {                      \
+        int opq;                                                                         \
+        asm volatile("s_mov_b32 %0, 0" : "=s"(opq));                                     \
+        const int g_ = g + opq, l32_ = l32 + opq;                                        \
+        const uint32_t rowb_ = (uint32_t)(N + opq) * 4u; /* bytes of one partial row */  \
+        const uint32_t voff_ = (uint32_t)(4 * g_) * rowb_ + l32_ * 4;                    \
+        _Pragma("unroll") for (int bm = 0; bm < BM; bm++) {                              \
+            f32x4 sc[4];                                                                 \
+            _Pragma("unroll") for (int q = 0; q < 4; q++)                                \
+                sc[q] = *reinterpret_cast<const f32x4*>(                                 \
+                    &ldsb[(buf) + ROWS * PITCH + (bm * 32 + 8 * q + 4 * g_) * 4]);       \
+            _Pragma("unroll") for (int i = 0; i < NS; i++) {                             \
+                const int st_ = t_cur * TSUB + wave * NS + i;                            \
+                if (st_ < n_sub) {                                                       \
+                    uint32_t so_ = (uint32_t)(slot * pl.rows + row0 + bm * 32) * rowb_ + st_ * 128; \
                     _Pragma("unroll") for (int r = 0; r < 16; r++) {                     \
-                        const int b_ = row0 + bm * 32 + 8 * (r >> 2) + 4 * g + (r & 3);  \
-                        if (b_ < B)                                                      \
-                            part[((size_t)slot_ * B + b_) * N + n_] = accl[(i * BM + bm) * 16 + r][tid]; \
+                        float v_ = (float)iacc[0][i][bm][r];                             \
+                        _Pragma("unroll") for (int p = 1; p < ND; p++)                   \
+                            v_ = v_ * 256.0f + (float)iacc[p][i][bm][r];                 \
+                        __builtin_amdgcn_raw_buffer_store_b32(                           \
+                            __builtin_bit_cast(uint32_t, sc[r >> 2][r & 3] * v_), p_rs, voff_, so_, 0); \
+                        so_ += (r & 3) == 3 ? 5 * rowb_ : rowb_; /* rows 8*(r/4) + 4*g + r%4 */ \
+                        if ((r & 3) == 3) __builtin_amdgcn_sched_barrier(0); /* few values in flight */ \
                     }                                                                    \
-                    __builtin_amdgcn_sched_barrier(0);                                   \
                 }                                                                        \
+                __builtin_amdgcn_sched_barrier(0); /* one tile at a time: bounded live set */ \
             }                                                                            \
-            _Pragma("unroll") for (int bm = 0; bm < BM; bm++)                            \
-                _Pragma("unroll") for (int r = 0; r < 16; r++)                           \
-                    accl[(i * BM + bm) * 16 + r][tid] = 0.f;                             \
         }                                                                                \
     }
-    // One unit: fetch the next activation stage into registers, multiply the current
-    // one, refill the ring slot just consumed, close a scale block / tile if this
-    // unit ended one (the scales are read before the barrier: afterwards another
-    // wave may already overwrite this stage), publish the next stage.
+    // One unit.  LDS holds three activation stages: stage k%3 is read by step k,
+    // stage (k+1)%3 was published by the previous barrier, stage (k+2)%3 (last read
+    // in step k-1) is written during step k.  The only thing a step waits for at its
+    // barrier is the other waves: its own LDS writes have a whole step to land, and
+    // the first operand reads of the next step are already in flight across it.
 #define PD_STEP(s)                                                                       \
     {                                                                                    \
-        PD_LOAD_A((s) % 2)                                                               \
+        PD_T(t0_)                                                                        \
+        PD_TACC(dbg_top, dbg_last, t0_)                                                  \
+        const int nxt_ = o_nxt, wr_ = o_wr;                                              \
+        PD_MFMA(cur, (s) % R, wr_, (s) % 2, ((s) + 1) % 2)                               \
+        PD_T(t1_)                                                                        \
+        PD_TACC(dbg_mfma, t0_, t1_)                                                      \
         __builtin_amdgcn_sched_barrier(0);                                               \
-        PD_MFMA(cur, s)                                                                  \
-        c_cur++;                                                                         \
-        u++;                                                                             \
-        if (c_cur == seg_end || u == u1) {                                               \
-            PD_FOLD(cur)                                                                 \
-            if (c_cur == C || u == u1) {                                                 \
-                PD_STORE_TILE()                                                          \
-                if (c_cur == C) { c_cur = 0; t_cur++; }                                  \
-            }                                                                            \
-            seg_end = block_end(c_cur);                                                  \
-        }                                                                                \
+        _Pragma("unroll") for (int g_ = 0; g_ < AD - 1; g_++) { PD_A_READ(nxt_, g_, g_) } \
         __builtin_amdgcn_sched_barrier(0);                                               \
-        PD_STORE_A(cur ^ 1, ((s) + 1) % 2)                                               \
-        lds_barrier();                                                                   \
-        cur ^= 1;                                                                        \
+        PD_T(t2_)                                                                        \
+        PD_TACC(dbg_mid, t1_, t2_)                                                       \
+        /* LDS operations of a wave complete in order: all but the (AD-1)*BM reads just */ \
+        /* issued, i.e. this step's stage writes, have landed before the barrier      */  \
+        asm volatile("s_waitcnt lgkmcnt(%0)\n\ts_barrier" ::"n"((AD - 1) * BM) : "memory"); \
+        last = cur;                                                                      \
+        o_wr = cur;                                                                      \
+        cur = nxt_;                                                                      \
+        o_nxt = wr_;                                                                     \
+        PD_T(t3_)                                                                        \
+        PD_TACC(dbg_bar, t2_, t3_)                                                       \
+        PD_TACC(dbg_last, dbg_last, t3_)                                                 \
     }
-
-    // prologue: activations of the first unit straight into stage 0, those of the
-    // second into register stage 1 (where step 0 expects them), R weight units in flight
-    {
-        const unsigned char* base_ = qa + (size_t)c_a * (ND * KC);
-#pragma unroll
-        for (int it = 0; it < APT; it++) areg[0][it] = *reinterpret_cast<const u32x4*>(base_ + aoff[it]);
-        if (tid < ROWS) sreg[0] = scale_t[(size_t)c_a * QSCALE_ROWS + srow];
-    }
-    PD_STORE_A(0, 0)
-    PD_LOAD_A(1)
-    PD_FETCH_W(0)
-    PD_FETCH_W(1)
-    if constexpr (R > 2) { PD_FETCH_W(2) }
-    if constexpr (R > 3) { PD_FETCH_W(3) }
-    if constexpr (R > 4) { PD_FETCH_W(4) }
-    if constexpr (R > 5) { PD_FETCH_W(5) }
-    lds_barrier();
-
-    int cur = 0;
+#ifdef PD_DBG_TIMING
+    long long dbg_top = 0, dbg_mfma = 0, dbg_mid = 0, dbg_bar = 0, dbg_x1 = 0, dbg_x2 = 0, dbg_last = clock64();
+    const long long dbg_t0 = dbg_last, dbg_w0 = wall_clock64();
+#endif
+    // One iteration per segment: clear the accumulators, run the segment's units,
+    // turn the int32 sums into one scaled fp32 partial.  (A fold inside the unit loop
+    // would put VALU reads and writes of the accumulators on the loop's back edge and
+    // the register allocator would then keep all of them in VGPRs.)  The weight ring
+    // and the activation stages run on across a segment end as long as the segment
+    // was a whole number of turns of the ring -- which the plan arranges for the
+    // decode shapes by starting workgroup ranges at multiples of R; otherwise the
+    // pipeline is filled again.
+    // byte offsets of the LDS stages: being read, published by the last barrier,
+    // being written; they rotate every step
+    unsigned char* const ldsb = &lds[0][0];
+    bool primed = false;
+    int cur = 0, o_nxt = STAGE, o_wr = 2 * STAGE, last = 0;
     for (;;) {
-        PD_STEP(0)
+        const int rest = u1 - u;
+        const int n_units = seg_end - c_cur < rest ? seg_end - c_cur : rest;
+#pragma unroll
+        for (int p = 0; p < ND; p++)
+#pragma unroll
+            for (int i = 0; i < NS; i++)
+#pragma unroll
+                for (int bm = 0; bm < BM; bm++)
+                    iacc[p][i][bm] = __builtin_amdgcn_mfma_i32_32x32x32_i8(zero4, zero4, zero16, 0, 0, 0);
+        if (!primed) {
+            // fill: activations of the first two units straight into stages 0 and 1,
+            // those of the third into register stage 1 (step 0 writes them to stage 2),
+            // R weight units in flight, first operand reads of step 0
+            t_w = t_cur; c_w = c_cur; c_a = c_cur;
+            u_w = u; u_a = u;
+            a_so = (uint32_t)c_cur * (ND * KC);
+            s_so = (uint32_t)c_cur * (QSCALE_ROWS * 4);
+            PD_W_PTRS()
+            PD_A_NOW(0)
+            PD_LOAD_A(1)
+            PD_STORE_A(0, 0)
+            PD_STORE_A(STAGE, 1)
+            PD_FETCH_W(0)
+            PD_FETCH_W(1)
+            if constexpr (R > 2) { PD_FETCH_W(2) }
+            if constexpr (R > 3) { PD_FETCH_W(3) }
+            // (issued after the weights so that, as in the loop, every weight load has
+            // these behind it: the compiler's wait counts at the loop head take the
+            // smaller of the two paths)
+            PD_LOAD_A(1)
+            lds_barrier();
+            cur = 0; o_nxt = STAGE; o_wr = 2 * STAGE;
+#pragma unroll
+            for (int g_ = 0; g_ < AD - 1; g_++) { PD_A_READ(0, g_, g_) }
+        }
+
+        // whole turns of the ring in a loop with a single exit (exits from the middle
+        // of the body make the compiler funnel scalar state through vector registers
+        // that have loads in flight, and wait for those), then the last R - 1 units at most
+        for (int turns = n_units / R; turns > 0; --turns) {
+            PD_STEP(0)
+            PD_STEP(1)
+            if constexpr (R > 2) {
+                PD_STEP(2)
+                PD_STEP(3)
+            }
+        }
+        const int rem = n_units % R;
+        if (rem > 0) {
+            PD_STEP(0)
+            if constexpr (R > 2) {
+                if (rem > 1) {
+                    PD_STEP(1)
+                    if (rem > 2) { PD_STEP(2) }
+                }
+            }
+        }
+        primed = rem == 0;
+        u += n_units;
+        c_cur += n_units;
+        // scales of the segment's scale block, from the stage of its last unit; the
+        // barrier keeps the next unit's stage write (or the next fill) from overwriting
+        // a stage that a slower wave is still reading
+        PD_CLOSE_SEGMENT(last)
+        lds_barrier();
         if (u == u1) break;
-        PD_STEP(1)
-        if (u == u1) break;
-        if constexpr (R > 2) {
-            PD_STEP(2)
-            if (u == u1) break;
-        }
-        if constexpr (R > 3) {
-            PD_STEP(3)
-            if (u == u1) break;
-        }
-        if constexpr (R > 4) {
-            PD_STEP(4)
-            if (u == u1) break;
-        }
-        if constexpr (R > 5) {
-            PD_STEP(5)
-            if (u == u1) break;
-        }
+        slot++;
+        if (c_cur == C) { c_cur = 0; t_cur++; slot = 0; }
+        seg_end = block_end(c_cur);
     }
+#ifdef PD_DBG_TIMING
+    if (tid == 0 && blockIdx.y == 0 && blockIdx.x < 2048) {
+        long long* d_ = pd_dbg + (c_split ? 2048 * 8 : 0) + blockIdx.x * 8;
+        d_[0] = clock64() - dbg_t0; d_[1] = wall_clock64() - dbg_w0; d_[2] = dbg_top; d_[3] = dbg_mfma;
+        d_[4] = dbg_mid; d_[5] = dbg_bar; d_[6] = u1 - u0; d_[7] = dbg_x1 * 100000 + dbg_x2 / 16;
+    }
+#endif
 #undef PD_FETCH_W
+#undef PD_A_NEXT
+#undef PD_A_NOW
 #undef PD_W_PTRS
 #undef PD_W_LOAD
+#undef PD_W_REFILL
 #undef PD_W_NEXT
 #undef PD_A_READ
 #undef PD_LOAD_A
 #undef PD_STORE_A
 #undef PD_MFMA
-#undef PD_FOLD
-#undef PD_STORE_TILE
+#undef PD_MFMA1
+#undef PD_CLOSE_SEGMENT
 #undef PD_STEP
+}
+
+// segments (= partial slots) per tile, for the consumers of the partial sums
+__global__ __launch_bounds__(256) void skq_table_kernel(SkqPlan pl, int* __restrict__ nseg) {
+    const int t = blockIdx.x * 256 + threadIdx.x;
+    if (t < pl.T) nseg[t] = skq_segments(t, pl);
 }
 
 // bf16 [B][K] -> block fixed point (test entry pd_qgemm): one wave per (row, chunk)
@@ -396,9 +554,9 @@ __global__ __launch_bounds__(256) void qgemm_reduce_kernel(const float* __restri
                                                            SkqPlan pl) {
     int n = blockIdx.x * 256 + threadIdx.x, b = blockIdx.y;
     if (n >= N) return;
-    const int ns = skq_slots(n / pl.tile_cols, pl.C, pl.T, pl.G);
+    const int ns = pl.nseg[n / pl.tile_cols];
     float acc = 0.f;
-    for (int s = 0; s < ns; s++) acc += part[((size_t)s * B + b) * N + n];
+    for (int s = 0; s < ns; s++) acc += part[((size_t)s * pl.rows + b) * N + n];
     out[(size_t)b * N + n] = scale[n] * acc;
 }
 
@@ -407,60 +565,80 @@ __global__ __launch_bounds__(256) void qgemm_reduce_kernel(const float* __restri
 void qgemm_config(int B, int* bm, int* ns, int* tile_cols) {
     int blocks = (B + 31) / 32;
     *bm = blocks <= 1 ? 1 : 2;  // more than 64 rows: several row groups
-    *ns = 1;
+    *ns = 2;
     *tile_cols = (NT / 64) * 32 * *ns;
 }
 
-SkqPlan qgemm_skq(int B, int K, int N, int G) {
+// Plan of a [K][N] projection for batch B: `workgroups` share the matrix (capped by
+// the number of units); returns the largest number of segments in any tile.
+SkqPlan qgemm_plan(int B, int K, int N, int workgroups, int c_split, int blk0, int blk1,
+                   int* max_slots) {
     int bm, ns, tc;
     qgemm_config(B, &bm, &ns, &tc);
-    return SkqPlan{tc, K / 128, (N + tc - 1) / tc, G};
-}
-
-// Workgroups per row group and partial slots per tile for a [K][N] projection.
-void qgemm_plan(int B, int K, int N, int num_cus, int* G, int* slots) {
-    int bm, ns, tc;
-    qgemm_config(B, &bm, &ns, &tc);
-    const int T = (N + tc - 1) / tc, C = K / 128;
-    const long long U = (long long)T * C;
-    long long g = num_cus;
-    if (g > U) g = U;
-    // a tile is shared by at most ceil(G / T) + 1 workgroups: keep that within PD_MAX_SPLITS
-    const long long cap = (long long)(PD_MAX_SPLITS - 1) * T;
-    if (g > cap) g = cap;
-    if (g < 1) g = 1;
+    SkqPlan pl;
+    pl.tile_cols = tc;
+    pl.C = K / 128;
+    pl.T = (N + tc - 1) / tc;
+    const long long U = (long long)pl.T * pl.C;
+    pl.G = (int)(workgroups < U ? (workgroups < 1 ? 1 : workgroups) : U);
+    // ranges that start at multiples of the weight ring (4 units) keep the pipeline of
+    // the unit loop running across segment ends; only worth it for ranges of many units
+    pl.align = (U / pl.G >= 16 && pl.C % 4 == 0 && c_split % 4 == 0 && (c_split == 0 || blk0 % 4 == 0) && blk1 % 4 == 0) ? 4 : 1;
+    pl.c_split = c_split;
+    pl.blk0 = blk0;
+    pl.blk1 = blk1;
+    pl.nseg = nullptr;
+    pl.rows = (B + 32 * bm - 1) / (32 * bm) * (32 * bm);
     int mx = 1;
-    for (int t = 0; t < T; t++) {
-        int n = skq_owner((long long)(t + 1) * C - 1, U, (int)g) - skq_owner((long long)t * C, U, (int)g) + 1;
+    for (int t = 0; t < pl.T; t++) {
+        const int n = skq_segments(t, pl);
         if (n > mx) mx = n;
     }
-    *G = (int)g;
-    *slots = mx;
+    pl.max_slots = mx;
+    if (max_slots) *max_slots = mx;
+    return pl;
+}
+
+hipError_t launch_skq_table(SkqPlan pl, int* nseg, hipStream_t stream) {
+    skq_table_kernel<<<dim3((pl.T + 255) / 256), dim3(256), 0, stream>>>(pl, nseg);
+    return hipGetLastError();
 }
 
 hipError_t launch_qgemm(const void* wp, const void* qa, const float* scale_t, float* part, int B,
-                        int K, int N, int G, int c_split, int blk0, int blk1, int nd,
-                        hipStream_t stream) {
+                        int K, int N, SkqPlan pl, int nd, hipStream_t stream) {
     int bm, ns, tc;
     qgemm_config(B, &bm, &ns, &tc);
-    dim3 grid(G, (B + 32 * bm - 1) / (32 * bm)), block(NT);
+    dim3 grid(pl.G, (B + 32 * bm - 1) / (32 * bm)), block(NT);
     const uint4* w4 = reinterpret_cast<const uint4*>(wp);
     const unsigned char* q = reinterpret_cast<const unsigned char*>(qa);
-#define PD_LAUNCH(BMv, NSv, PD_RING)                                                                 \
+#define PD_LAUNCH(BMv, NSv, RING, ADv)                                                           \
     do {                                                                                    \
         if (nd == 3)                                                                        \
-            qgemm_kernel<BMv, NSv, 3, PD_RING><<<grid, block, 0, stream>>>(w4, q, scale_t, part, B, K, N, c_split, blk0, blk1); \
+            qgemm_kernel<BMv, NSv, 3, RING, ADv><<<grid, block, 0, stream>>>(w4, q, scale_t, part, B, K, N, pl); \
         else                                                                                \
-            qgemm_kernel<BMv, NSv, 2, PD_RING><<<grid, block, 0, stream>>>(w4, q, scale_t, part, B, K, N, c_split, blk0, blk1); \
+            qgemm_kernel<BMv, NSv, 2, RING, ADv><<<grid, block, 0, stream>>>(w4, q, scale_t, part, B, K, N, pl); \
     } while (0)
     if (nd != 2 && nd != 3) return hipErrorInvalidValue;
-    if (blk0 < 1 || blk0 > 1024 || blk1 < 1 || blk1 > 1024 || c_split < 0 || c_split > K / 128)
+    if (pl.blk0 < 1 || pl.blk0 > 1024 || pl.blk1 < 1 || pl.blk1 > 1024 || pl.c_split < 0 || pl.c_split > K / 128)
         return hipErrorInvalidValue;
-    if (bm == 1) PD_LAUNCH(1, 1, 6);
-    else PD_LAUNCH(2, 1, 2);
+    // buffer descriptors address 32 bits
+    if ((long long)B * K * nd >= (1ll << 31) || (long long)K * N >= (1ll << 32)) return hipErrorInvalidValue;
+    if ((long long)pl.T * pl.C >= (1ll << 31)) return hipErrorInvalidValue;
+    if ((long long)pl.max_slots * pl.rows * N * 4 >= (1ll << 32)) return hipErrorInvalidValue;
+    const char* ring_env = getenv("PD_GEMM_RING");  // tuning only
+    const int ring = ring_env ? atoi(ring_env) : 0;
+    if (bm == 1) PD_LAUNCH(1, 2, 4, 4);
+    else if (ring == 4) PD_LAUNCH(2, 2, 4, 3);
+    else PD_LAUNCH(2, 2, 2, 5);
 #undef PD_LAUNCH
     return hipGetLastError();
 }
+
+#ifdef PD_DBG_TIMING
+extern "C" int pd_dbg_read(long long* host, int n) {
+    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(pd_dbg), sizeof(long long) * n);
+}
+#endif
 
 hipError_t launch_quantize_bf16(const uint16_t* a, void* qa, float* scale_t, int B, int K, int nd,
                                 hipStream_t stream) {
@@ -483,10 +661,9 @@ hipError_t launch_pack_vector(const uint16_t* src, float* dst, int N, int mode, 
     return hipGetLastError();
 }
 
-hipError_t launch_qgemm_reduce(const float* part, const float* scale, float* out, int B, int K,
-                               int N, int G, hipStream_t stream) {
-    qgemm_reduce_kernel<<<dim3((N + 255) / 256, B), dim3(256), 0, stream>>>(
-        part, scale, out, B, N, qgemm_skq(B, K, N, G));
+hipError_t launch_qgemm_reduce(const float* part, const float* scale, float* out, int B, int N,
+                               SkqPlan pl, hipStream_t stream) {
+    qgemm_reduce_kernel<<<dim3((N + 255) / 256, B), dim3(256), 0, stream>>>(part, scale, out, B, N, pl);
     return hipGetLastError();
 }
 

@@ -89,13 +89,13 @@ def test_kv_layout_import_export_bit_exact(pd, dh, B, L):
 
 # ------------------------------------------------------------------- GEMM ---
 
-def run_qgemm(pd, a_bf16, w_i8, scale_f32, k_splits):
+def run_qgemm(pd, a_bf16, w_i8, scale_f32, k_splits):  # k_splits = workgroups sharing the matrix
     from paper_2211_05102_amd import binding
     B, K = a_bf16.shape
     N = w_i8.shape[1]
     packed = torch.empty(K * N, dtype=torch.uint8, device="cuda")
     binding.pack_matrix(w_i8.cuda().contiguous(), packed)
-    ws = torch.empty(binding.qgemm_workspace_bytes(B, K, N), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(binding.qgemm_workspace_bytes(B, K, N, k_splits), dtype=torch.uint8, device="cuda")
     out = torch.full((B, N), float("nan"), dtype=torch.float32, device="cuda")
     binding.qgemm(packed, scale_f32.cuda(), a_bf16.cuda().contiguous(), N, out, ws, k_splits)
     torch.cuda.synchronize()
