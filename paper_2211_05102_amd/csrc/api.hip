@@ -134,14 +134,14 @@ Workspace workspace_layout(const Shape& s, int B, int L_ctx) {
     w.h = o; o += align256((size_t)B * s.d * 3);                    // digit planes of LN(x)
     w.hs = o; o += align256((size_t)(s.d / 128) * 256 * 4);         // their scales [chunk][256]
     w.part_in = o; o += align256((size_t)slots_bound(gp.in) * gp.in.rows * s.n_in * 4);
-    w.nseg_in = o; o += align256((size_t)gp.in.T * 4);
+    w.nseg_in = o; o += align256(pd::skq_table_ints(gp.in.T, PD_GEMM_WORKGROUPS) * 4);
     w.q = o; o += align256((size_t)B * s.H * s.dh * 4);
     w.act = o; o += align256((size_t)B * s.k_out * 3);              // digit planes of [o | a]
     w.acts = o; o += align256((size_t)(s.k_out / 128) * 256 * 4);
     w.opart = o; o += align256((size_t)B * nsplit_max * s.H * s.dh * 4);
     w.ml = o; o += align256((size_t)B * nsplit_max * s.H * 2 * 4);
     w.part_out = o; o += align256((size_t)slots_bound(gp.out) * gp.out.rows * s.d * 4);
-    w.nseg_out = o; o += align256((size_t)gp.out.T * 4);
+    w.nseg_out = o; o += align256(pd::skq_table_ints(gp.out.T, PD_GEMM_WORKGROUPS) * 4);
     w.stats = o; o += align256((size_t)B * ((s.d + 1023) / 1024) * 4 * 4);  // LayerNorm slice statistics
     w.total = o;
     return w;
@@ -515,7 +515,7 @@ QgemmWs qgemm_ws(int B, int K, int N, int workgroups) {
     q.part = o; o += align256((size_t)slots * q.pl.rows * N * 4);
     q.qa = o; o += align256((size_t)B * K * 3);
     q.qs = o; o += align256((size_t)(K / 128) * 256 * 4);
-    q.nseg = o; o += align256((size_t)q.pl.T * 4);
+    q.nseg = o; o += align256(pd::skq_table_ints(q.pl.T, q.pl.G) * 4);
     q.total = o;
     return q;
 }

@@ -20,17 +20,18 @@ constexpr int WAVE = 64;
 // chunk), ordered tile-major; workgroup g of G takes the contiguous unit range
 // [g*U/G, (g+1)*U/G), U = T*C.  Inside a tile the chunks are also grouped into
 // scale blocks (chunks [0, c_split) in blocks of blk0, chunks [c_split, C) in
-// blocks of blk1).  A SEGMENT is a maximal run of chunks of one tile that lies in
-// one workgroup's range and in one scale block; every segment produces one fp32
-// partial of the tile, stored in slot = index of the segment inside the tile, and
-// consumers add the slots of a tile in index order: results do not depend on timing.
+// blocks of blk1) over which the exact int32 sums run on; at the end of a block
+// they are folded into fp32 tile accumulators.  The part of a tile that lies in one
+// workgroup's range produces one fp32 partial of the tile, stored in slot = index
+// of that workgroup among those that share the tile, and consumers add the slots of
+// a tile in index order: results do not depend on timing.
 struct SkqPlan {
     int tile_cols, C, T, G;
     int c_split, blk0, blk1;
     int align;        // workgroup ranges start at multiples of this many units
     int rows;         // rows of one partial slot: the batch rounded up to whole row groups
-    int max_slots;    // most segments in any tile
-    const int* nseg;  // device: segments per tile (skq_table_kernel)
+    int max_slots;    // most slots in any tile
+    const int* nseg;  // device table (skq_table_kernel): slots per tile, then one record per workgroup
 };
 // First unit of workgroup g's range (g = G: one past the last unit).
 __host__ __device__ inline long long skq_begin(int g, long long U, int G, int align) {
@@ -43,31 +44,29 @@ __host__ __device__ inline int skq_owner(long long u, long long U, int G, int al
     if (g + 1 < G && skq_begin(g + 1, U, G, align) <= u) g++;
     return g;
 }
-// Is chunk position p in (0, C) the first chunk of a scale block?
-__host__ __device__ inline bool skq_block_start(int p, int c_split, int blk0, int blk1) {
-    if (p < c_split) return p % blk0 == 0;
-    return (p - c_split) % blk1 == 0;
-}
-// Segments of tile t that start at a chunk position in (0, c], c <= C - 1: the slot
-// of a segment that starts at chunk c (0 for c = 0).
+// Workgroup ranges that start at a chunk position in (0, c] of tile t, c <= C - 1:
+// the slot of the range that holds chunk c.
 __host__ __device__ inline int skq_segments_upto(int t, int c, const SkqPlan& pl) {
     if (c <= 0) return 0;
     int n = 0;
-    if (pl.c_split > 0) n += (c < pl.c_split - 1 ? c : pl.c_split - 1) / pl.blk0;  // starts below c_split
-    if (pl.c_split > 0 && pl.c_split <= c) n += 1;                                  // c_split itself
-    if (c > pl.c_split) n += (c - pl.c_split) / pl.blk1;                            // starts above it
-    // workgroup range starts inside (0, c] that are not scale-block starts
     const long long U = (long long)pl.T * pl.C, base = (long long)t * pl.C;
     for (int g = skq_owner(base, U, pl.G, pl.align) + 1; g < pl.G; g++) {
         const long long pos = skq_begin(g, U, pl.G, pl.align) - base;
         if (pos > c) break;
-        if (pos > 0 && !skq_block_start((int)pos, pl.c_split, pl.blk0, pl.blk1)) n++;
+        if (pos > 0) n++;
     }
     return n;
 }
+// slots of tile t
 __host__ __device__ inline int skq_segments(int t, const SkqPlan& pl) {
     return skq_segments_upto(t, pl.C - 1, pl) + 1;
 }
+
+// Device table of a plan, in ints: [0, T) slots per tile; from skq_wg_offset(T), four
+// per workgroup g: first unit, one past the last unit, slot of its range in its first
+// tile, first tile.
+__host__ __device__ inline int skq_wg_offset(int T) { return (T + 3) & ~3; }
+__host__ __device__ inline size_t skq_table_ints(int T, int G) { return (size_t)skq_wg_offset(T) + 4 * (size_t)G; }
 
 // round-to-nearest-even fp32 -> bf16 bit pattern (v_cvt_pk_bf16_f32 on gfx950)
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {

@@ -85,22 +85,29 @@ __global__ __launch_bounds__(NT) void qgemm_kernel(const uint4* __restrict__ wp,
     constexpr int STAGE = ROWS * PITCH + ROWS * 4;  // digits + one scale per row
     static_assert(3 + APT < KB * ND, "stage write fits behind the loads in one unit");
     static_assert(R == 2 || R == 4, "ring depth (even: the activation register stages alternate with the ring slots)");
-    static_assert(3 * STAGE <= 160 * 1024, "LDS");
+    static_assert(3 * STAGE + NS * BM * 16 * NT * 4 <= 160 * 1024, "LDS");
     __shared__ __attribute__((aligned(16))) unsigned char lds[3][STAGE];
+    // fp32 sums of the scale blocks of the current tile that this range has finished:
+    // thread-private (each thread owns 16 * NS * BM values), kept in LDS because the
+    // unit loop leaves no registers for them
+    __shared__ f32x4 accl[NS * BM * 4][NT];
 
+#ifdef PD_DBG_TIMING
+    const long long dbg_k0 = clock64();
+#endif
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform: lets addresses stay scalar
     const int g = lane >> 5, l32 = lane & 31;
     const int n_sub = N >> 5;
-    const int C = pl.C, T = pl.T, G = pl.G;
+    const int C = pl.C, T = pl.T;
     const int c_split = pl.c_split, blk0 = pl.blk0, blk1 = pl.blk1;
-    const long long U = (long long)T * C;
-    // (32-bit from here on: the launcher rejects U >= 2^31, and 64-bit compares would run on the vector ALU)
-    // Integer division runs on the vector ALU and leaves its (uniform) result in a
-    // vector register; readfirstlane moves it to a scalar one so that everything
-    // derived from it -- unit counters, buffer offsets, loop exits -- stays scalar.
-    const int u0 = __builtin_amdgcn_readfirstlane((int)skq_begin(blockIdx.x, U, G, pl.align));
-    const int u1 = __builtin_amdgcn_readfirstlane((int)skq_begin(blockIdx.x + 1, U, G, pl.align));
+    // This workgroup's range comes from the plan's device table (the divisions that
+    // define it are 64-bit and would run on the vector ALU, here, in every launch).
+    // Scalar loads: everything derived from them -- unit counters, buffer offsets,
+    // loop exits -- stays scalar.
+    const int* rec = pl.nseg + skq_wg_offset(T) + 4 * (int)blockIdx.x;
+    const int u0 = __builtin_amdgcn_readfirstlane(rec[0]);
+    const int u1 = __builtin_amdgcn_readfirstlane(rec[1]);
     if (u0 >= u1) return;
     const int row0 = blockIdx.y * ROWS;
 
@@ -160,6 +167,9 @@ __global__ __launch_bounds__(NT) void qgemm_kernel(const uint4* __restrict__ wp,
             for (int bm = 0; bm < BM; bm++)
                 iacc[p][i][bm] = __builtin_amdgcn_mfma_i32_32x32x32_i8(zero4, zero4, zero16, 0, 0, 0);
 
+#pragma unroll
+    for (int j = 0; j < NS * BM * 4; j++) accl[j][tid] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
     u32x4 wreg[R][NS][KB];
     u32x4 areg[2][APT];
     float sreg[2] = {0.f, 0.f};
@@ -167,11 +177,11 @@ __global__ __launch_bounds__(NT) void qgemm_kernel(const uint4* __restrict__ wp,
 
     // (tile, chunk) of the unit being computed; of the next weight unit to fetch
     // (saturates at the last unit of the range); chunk of the next activation stage
-    int t_cur = __builtin_amdgcn_readfirstlane(u0 / C);
+    int t_cur = __builtin_amdgcn_readfirstlane(rec[3]);
     int c_cur = u0 - t_cur * C;
     int t_w = t_cur, c_w = c_cur, c_a = c_cur;
     int u = u0, u_w = u0, u_a = u0;
-    int slot = __builtin_amdgcn_readfirstlane(skq_segments_upto(t_cur, c_cur, pl));  // partial slot of the segment being accumulated
+    int slot = __builtin_amdgcn_readfirstlane(rec[2]);  // partial slot of this range in tile t_cur
 
     // end of the scale block that holds chunk c
     auto block_end = [&](int c) {
@@ -310,40 +320,74 @@ __global__ __launch_bounds__(NT) void qgemm_kernel(const uint4* __restrict__ wp,
         }                                                                                \
         PD_W_NEXT()                                                                      \
     }
-    // A segment ends: part[slot] = scale * sum_p 256^(ND-1-p) * float(iacc[p]).
+    // A scale block ends: facc += scale * sum_p 256^(ND-1-p) * float(iacc[p]).
     // int32 bound per plane and scale block: 128 * 127 * 128 * chunks < 2^31 for blocks
     // of up to 1024 chunks.  D layout of the 32x32 MFMA: register r of lane (l32, g)
     // is row 8*(r/4) + 4*g + r%4, column l32.
-    // (`opq` is a zero the compiler cannot see through: everything the stores need is
-    // computed from it, here, instead of being hoisted above the unit loop and kept in
-    // registers across it.)
-#define PD_CLOSE_SEGMENT(buf)                                                            \
+    // (`opq` is a zero the compiler cannot see through: what the fold and the stores
+    // need is computed from it, here, instead of being hoisted above the unit loop and
+    // kept in registers across it.)
+#define PD_FOLD(buf)                                                                     \
     {                                                                                    \
         int opq;                                                                         \
         asm volatile("s_mov_b32 %0, 0" : "=s"(opq));                                     \
-        const int g_ = g + opq, l32_ = l32 + opq;                                        \
-        const uint32_t rowb_ = (uint32_t)(N + opq) * 4u; /* bytes of one partial row */  \
-        const uint32_t voff_ = (uint32_t)(4 * g_) * rowb_ + l32_ * 4;                    \
+        const int g_ = g + opq, tid_ = tid + opq;                                        \
+        /* the running sums are read one group of four ahead of their use */             \
+        f32x4 nx_ = accl[0][tid_];                                                       \
         _Pragma("unroll") for (int bm = 0; bm < BM; bm++) {                              \
             f32x4 sc[4];                                                                 \
             _Pragma("unroll") for (int q = 0; q < 4; q++)                                \
                 sc[q] = *reinterpret_cast<const f32x4*>(                                 \
                     &ldsb[(buf) + ROWS * PITCH + (bm * 32 + 8 * q + 4 * g_) * 4]);       \
             _Pragma("unroll") for (int i = 0; i < NS; i++) {                             \
+                /* The accumulators leave their AGPRs one 32x32 tile at a time, through */ \
+                /* an MFMA of zeros that adds them into VGPRs.  (Read by vector ALU     */ \
+                /* code directly, the register allocator copies all of them to VGPRs at */ \
+                /* the loop exit and spills what the unit loop keeps there.)            */ \
+                i32x16 c_[ND];                                                           \
+                _Pragma("unroll") for (int p = 0; p < ND; p++)                           \
+                    c_[p] = __builtin_amdgcn_mfma_i32_32x32x32_i8(zero4, zero4, iacc[p][i][bm], 0, 0, 0); \
+                _Pragma("unroll") for (int q = 0; q < 4; q++) {                          \
+                    const int j_ = (bm * NS + i) * 4 + q;                                \
+                    f32x4 t_ = nx_;                                                      \
+                    if (j_ + 1 < NS * BM * 4) nx_ = accl[j_ + 1][tid_];                  \
+                    _Pragma("unroll") for (int k = 0; k < 4; k++) {                      \
+                        float v_ = (float)c_[0][4 * q + k];                              \
+                        _Pragma("unroll") for (int p = 1; p < ND; p++)                   \
+                            v_ = v_ * 256.0f + (float)c_[p][4 * q + k];                  \
+                        t_[k] += sc[q][k] * v_;                                          \
+                    }                                                                    \
+                    accl[j_][tid_] = t_;                                                 \
+                }                                                                        \
+                __builtin_amdgcn_sched_barrier(0); /* one tile in flight */              \
+            }                                                                            \
+        }                                                                                \
+    }
+    // The range leaves the tile (or ends): part[slot] = tile sums, tile sums = 0.
+#define PD_STORE_TILE()                                                                  \
+    {                                                                                    \
+        int opq;                                                                         \
+        asm volatile("s_mov_b32 %0, 0" : "=s"(opq));                                     \
+        const int g_ = g + opq, l32_ = l32 + opq, tid_ = tid + opq;                      \
+        const uint32_t rowb_ = (uint32_t)(N + opq) * 4u; /* bytes of one partial row */  \
+        const uint32_t voff_ = (uint32_t)(4 * g_) * rowb_ + l32_ * 4;                    \
+        _Pragma("unroll") for (int bm = 0; bm < BM; bm++) {                              \
+            _Pragma("unroll") for (int i = 0; i < NS; i++) {                             \
                 const int st_ = t_cur * TSUB + wave * NS + i;                            \
                 if (st_ < n_sub) {                                                       \
                     uint32_t so_ = (uint32_t)(slot * pl.rows + row0 + bm * 32) * rowb_ + st_ * 128; \
-                    _Pragma("unroll") for (int r = 0; r < 16; r++) {                     \
-                        float v_ = (float)iacc[0][i][bm][r];                             \
-                        _Pragma("unroll") for (int p = 1; p < ND; p++)                   \
-                            v_ = v_ * 256.0f + (float)iacc[p][i][bm][r];                 \
-                        __builtin_amdgcn_raw_buffer_store_b32(                           \
-                            __builtin_bit_cast(uint32_t, sc[r >> 2][r & 3] * v_), p_rs, voff_, so_, 0); \
-                        so_ += (r & 3) == 3 ? 5 * rowb_ : rowb_; /* rows 8*(r/4) + 4*g + r%4 */ \
-                        if ((r & 3) == 3) __builtin_amdgcn_sched_barrier(0); /* few values in flight */ \
+                    _Pragma("unroll") for (int q = 0; q < 4; q++) {                      \
+                        const f32x4 t_ = accl[(bm * NS + i) * 4 + q][tid_];              \
+                        _Pragma("unroll") for (int k = 0; k < 4; k++) {                  \
+                            const float f_ = t_[k];                                      \
+                            __builtin_amdgcn_raw_buffer_store_b32(                       \
+                                __builtin_bit_cast(uint32_t, f_), p_rs, voff_, so_, 0);  \
+                            so_ += k == 3 ? 5 * rowb_ : rowb_; /* rows 8*q + 4*g + k */  \
+                        }                                                                \
                     }                                                                    \
                 }                                                                        \
-                __builtin_amdgcn_sched_barrier(0); /* one tile at a time: bounded live set */ \
+                _Pragma("unroll") for (int q = 0; q < 4; q++)                            \
+                    accl[(bm * NS + i) * 4 + q][tid_] = (f32x4){0.f, 0.f, 0.f, 0.f};     \
             }                                                                            \
         }                                                                                \
     }
@@ -379,6 +423,7 @@ __global__ __launch_bounds__(NT) void qgemm_kernel(const uint4* __restrict__ wp,
 #ifdef PD_DBG_TIMING
     long long dbg_top = 0, dbg_mfma = 0, dbg_mid = 0, dbg_bar = 0, dbg_x1 = 0, dbg_x2 = 0, dbg_last = clock64();
     const long long dbg_t0 = dbg_last, dbg_w0 = wall_clock64();
+    long long dbg_first = 0;
 #endif
     // One iteration per segment: clear the accumulators, run the segment's units,
     // turn the int32 sums into one scaled fp32 partial.  (A fold inside the unit loop
@@ -391,22 +436,37 @@ __global__ __launch_bounds__(NT) void qgemm_kernel(const uint4* __restrict__ wp,
     // byte offsets of the LDS stages: being read, published by the last barrier,
     // being written; they rotate every step
     unsigned char* const ldsb = &lds[0][0];
-    bool primed = false;
     int cur = 0, o_nxt = STAGE, o_wr = 2 * STAGE, last = 0;
-    for (;;) {
-        const int rest = u1 - u;
-        const int n_units = seg_end - c_cur < rest ? seg_end - c_cur : rest;
-#pragma unroll
-        for (int p = 0; p < ND; p++)
-#pragma unroll
-            for (int i = 0; i < NS; i++)
-#pragma unroll
-                for (int bm = 0; bm < BM; bm++)
-                    iacc[p][i][bm] = __builtin_amdgcn_mfma_i32_32x32x32_i8(zero4, zero4, zero16, 0, 0, 0);
-        if (!primed) {
+    // The end of a segment: scales of the segment's scale block from the stage of its
+    // last unit; the barrier keeps the next unit's stage write (or the next fill) from
+    // overwriting a stage that a slower wave is still reading.
+#define PD_END_SEGMENT()                                                                 \
+    u += n_units;                                                                        \
+    c_cur += n_units;                                                                    \
+    PD_FOLD(last)                                                                        \
+    if (c_cur == C || u == u1) { PD_STORE_TILE() }                                       \
+    lds_barrier();                                                                       \
+    if (u == u1) break;                                                                  \
+    if (c_cur == C) { c_cur = 0; t_cur++; slot = 0; }                                    \
+    seg_end = block_end(c_cur);
+    // Outer loop: fill the pipeline.  Inner loop: the segments that run on it -- it
+    // keeps running across a segment end as long as the segment was a whole number of
+    // turns of the ring, which the plan arranges for the decode shapes by starting
+    // workgroup ranges at multiples of the ring; a segment with a remainder ends in
+    // its own copy of the segment end and falls out to the fill.  (One copy behind
+    // an `if` would let the wait counts of the remainder steps, which have just
+    // refilled ring slot 0, reach the head of the unit loop, where slot 0 is read:
+    // every turn would then wait for nearly all of its loads.)
+    bool done = false;
+    while (!done) {
+        done = true;
+
             // fill: activations of the first two units straight into stages 0 and 1,
             // those of the third into register stage 1 (step 0 writes them to stage 2),
-            // R weight units in flight, first operand reads of step 0
+            // R weight units in flight, first operand reads of step 0.  (The weights are
+            // fetched after the wait for the first activations, not before: waiting for a
+            // younger load completes every older one, and the compiler would carry that
+            // into the wait counts at the head of the unit loop and drain the ring there.)
             t_w = t_cur; c_w = c_cur; c_a = c_cur;
             u_w = u; u_a = u;
             a_so = (uint32_t)c_cur * (ND * KC);
@@ -424,51 +484,63 @@ __global__ __launch_bounds__(NT) void qgemm_kernel(const uint4* __restrict__ wp,
             // these behind it: the compiler's wait counts at the loop head take the
             // smaller of the two paths)
             PD_LOAD_A(1)
+            // Everything fetched so far is waited for here, once, so that the compiler's
+            // wait counts at the head of the unit loop come from the loop's own back edge
+            // alone (merged with this path they drain the ring on every turn).
+            __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
             lds_barrier();
             cur = 0; o_nxt = STAGE; o_wr = 2 * STAGE;
 #pragma unroll
             for (int g_ = 0; g_ < AD - 1; g_++) { PD_A_READ(0, g_, g_) }
-        }
-
-        // whole turns of the ring in a loop with a single exit (exits from the middle
-        // of the body make the compiler funnel scalar state through vector registers
-        // that have loads in flight, and wait for those), then the last R - 1 units at most
-        for (int turns = n_units / R; turns > 0; --turns) {
-            PD_STEP(0)
-            PD_STEP(1)
-            if constexpr (R > 2) {
-                PD_STEP(2)
-                PD_STEP(3)
-            }
-        }
-        const int rem = n_units % R;
-        if (rem > 0) {
-            PD_STEP(0)
-            if constexpr (R > 2) {
-                if (rem > 1) {
-                    PD_STEP(1)
-                    if (rem > 2) { PD_STEP(2) }
+        
+        for (;;) {
+            const int rest = u1 - u;
+            const int n_units = seg_end - c_cur < rest ? seg_end - c_cur : rest;
+#pragma unroll
+            for (int p = 0; p < ND; p++)
+#pragma unroll
+                for (int i = 0; i < NS; i++)
+#pragma unroll
+                    for (int bm = 0; bm < BM; bm++)
+                        iacc[p][i][bm] = __builtin_amdgcn_mfma_i32_32x32x32_i8(zero4, zero4, zero16, 0, 0, 0);
+            // whole turns of the ring in a loop with a single exit (exits from the middle
+            // of the body make the compiler funnel scalar state through vector registers
+            // that have loads in flight, and wait for those), then the last R - 1 units at most
+            for (int turns = n_units / R; turns > 0; --turns) {
+                PD_STEP(0)
+                PD_STEP(1)
+                if constexpr (R > 2) {
+                    PD_STEP(2)
+                    PD_STEP(3)
                 }
             }
+            const int rem = n_units % R;
+            if (rem > 0) {
+                PD_STEP(0)
+                if constexpr (R > 2) {
+                    if (rem > 1) {
+                        PD_STEP(1)
+                        if (rem > 2) { PD_STEP(2) }
+                    }
+                }
+                // nothing stays in flight from here (the fill that follows waits for all
+                // of it anyway): the compiler then has no loads of the remainder steps to
+                // account for at the head of the unit loop, where it would otherwise wait
+                // for ring slot 0 -- just refilled here -- on every turn
+                __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+                PD_END_SEGMENT()
+                done = false;  // refill and go on
+                break;
+            }
+            PD_END_SEGMENT()
         }
-        primed = rem == 0;
-        u += n_units;
-        c_cur += n_units;
-        // scales of the segment's scale block, from the stage of its last unit; the
-        // barrier keeps the next unit's stage write (or the next fill) from overwriting
-        // a stage that a slower wave is still reading
-        PD_CLOSE_SEGMENT(last)
-        lds_barrier();
-        if (u == u1) break;
-        slot++;
-        if (c_cur == C) { c_cur = 0; t_cur++; slot = 0; }
-        seg_end = block_end(c_cur);
     }
+#undef PD_END_SEGMENT
 #ifdef PD_DBG_TIMING
     if (tid == 0 && blockIdx.y == 0 && blockIdx.x < 2048) {
         long long* d_ = pd_dbg + (c_split ? 2048 * 8 : 0) + blockIdx.x * 8;
         d_[0] = clock64() - dbg_t0; d_[1] = wall_clock64() - dbg_w0; d_[2] = dbg_top; d_[3] = dbg_mfma;
-        d_[4] = dbg_mid; d_[5] = dbg_bar; d_[6] = u1 - u0; d_[7] = dbg_x1 * 100000 + dbg_x2 / 16;
+        d_[4] = dbg_x1; d_[5] = dbg_x2; d_[6] = u1 - u0; d_[7] = dbg_first;
     }
 #endif
 #undef PD_FETCH_W
@@ -483,14 +555,25 @@ __global__ __launch_bounds__(NT) void qgemm_kernel(const uint4* __restrict__ wp,
 #undef PD_STORE_A
 #undef PD_MFMA
 #undef PD_MFMA1
-#undef PD_CLOSE_SEGMENT
+#undef PD_FOLD
+#undef PD_STORE_TILE
 #undef PD_STEP
 }
 
 // segments (= partial slots) per tile, for the consumers of the partial sums
-__global__ __launch_bounds__(256) void skq_table_kernel(SkqPlan pl, int* __restrict__ nseg) {
+__global__ __launch_bounds__(256) void skq_table_kernel(SkqPlan pl, int* __restrict__ table) {
     const int t = blockIdx.x * 256 + threadIdx.x;
-    if (t < pl.T) nseg[t] = skq_segments(t, pl);
+    if (t < pl.T) table[t] = skq_segments(t, pl);
+    if (t < pl.G) {
+        const long long U = (long long)pl.T * pl.C;
+        const long long u0 = skq_begin(t, U, pl.G, pl.align), u1 = skq_begin(t + 1, U, pl.G, pl.align);
+        const int t0 = (int)(u0 / pl.C);
+        int* rec = table + skq_wg_offset(pl.T) + 4 * t;
+        rec[0] = (int)u0;
+        rec[1] = (int)u1;
+        rec[2] = u0 < u1 ? skq_segments_upto(t0, (int)(u0 - (long long)t0 * pl.C), pl) : 0;
+        rec[3] = t0;
+    }
 }
 
 // bf16 [B][K] -> block fixed point (test entry pd_qgemm): one wave per (row, chunk)
@@ -600,7 +683,8 @@ SkqPlan qgemm_plan(int B, int K, int N, int workgroups, int c_split, int blk0, i
 }
 
 hipError_t launch_skq_table(SkqPlan pl, int* nseg, hipStream_t stream) {
-    skq_table_kernel<<<dim3((pl.T + 255) / 256), dim3(256), 0, stream>>>(pl, nseg);
+    const int n = pl.T > pl.G ? pl.T : pl.G;
+    skq_table_kernel<<<dim3((n + 255) / 256), dim3(256), 0, stream>>>(pl, nseg);
     return hipGetLastError();
 }
 
@@ -629,7 +713,9 @@ hipError_t launch_qgemm(const void* wp, const void* qa, const float* scale_t, fl
     const int ring = ring_env ? atoi(ring_env) : 0;
     if (bm == 1) PD_LAUNCH(1, 2, 4, 4);
     else if (ring == 4) PD_LAUNCH(2, 2, 4, 3);
-    else PD_LAUNCH(2, 2, 2, 5);
+    else if (ring == 5) PD_LAUNCH(2, 2, 2, 5);
+    else if (ring == 3) PD_LAUNCH(2, 2, 2, 3);
+    else PD_LAUNCH(2, 2, 2, 4);
 #undef PD_LAUNCH
     return hipGetLastError();
 }
