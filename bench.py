@@ -63,6 +63,12 @@ def cpu_baseline(w, stack_rows=4, seconds_budget=20.0):
     }
 
 
+# HBM bytes one launch of the input projection moves, from the rocprofv3 FETCH_SIZE / WRITE_SIZE passes
+# summarised in profiles/hbm_traffic_pmc_c3_62b_layer.txt (counters scaled by a plain 1 GiB copy):
+# (308869.5 * 2.0 + 33920.0 * 1.0) KiB.  Other workloads: not measured.
+TRAFFIC_BYTES_PER_LAUNCH = {"c3_62b": int((308869.5 * 2.0 + 33920.0) * 1024)}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -77,6 +83,9 @@ def main():
     ap.add_argument("--gemm-wg-out", type=int, default=0)
     ap.add_argument("--attn-bps", type=int, default=0)
     ap.add_argument("--act-digits", type=int, default=0)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run three plain 1 GiB device copies (reference for scaling rocprofv3's "
+                         "FETCH_SIZE / WRITE_SIZE counters in the --pmc passes)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus must be 1",
@@ -104,6 +113,13 @@ def main():
     flops_step = C.algorithmic_flops(w, positions)
 
     stream = torch.cuda.Stream()
+    if args.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(3)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     use_graph = not args.no_graph
     with torch.cuda.stream(stream):
         if use_graph:
@@ -164,7 +180,7 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "bf16",
+        "dtype": "int8",  # int8 x int8 -> int32 MFMA on block fixed-point activations; fp32 folds and softmax
         "data": "synthetic",
         "config": {"workload": w.name, "n_layers": w.n_layers, "d_model": w.d_model,
                    "n_heads": w.n_heads, "d_head": w.d_head, "d_ff": w.d_ff, "batch": w.batch,
@@ -172,7 +188,7 @@ def main():
                    "launch": "hipGraph replay" if use_graph else "eager", "setup_s": round(t_setup, 1)},
         "roofline": {"bound": "hbm", "kernel": "qgemm_kernel (fused input projection)",
                      "achieved": k_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": k_gbps / HBM_PEAK_GBPS, "traffic": None,
+                     "frac": k_gbps / HBM_PEAK_GBPS, "traffic": TRAFFIC_BYTES_PER_LAUNCH.get(args.workload),
                      "bytes_per_launch": k_bytes, "avg_launch_us": k_avg_s * 1e6},
         "kernels": per_kernel,
     }
