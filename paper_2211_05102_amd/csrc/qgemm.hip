@@ -8,11 +8,11 @@
 // of the partial sums, which is exact because it does not depend on k.
 //
 // Arithmetic.  Activations arrive in block fixed point (common.h): ND int8 digit
-// planes and a power-of-two scale per (row, 128-k chunk).  Every digit plane goes
-// through v_mfma_i32_32x32x32_i8 against the raw int8 weights -- no weight
-// conversion, exact int32 sums, one int32 accumulator per plane -- and every
-// `fold_chunks` chunks (over which the producer keeps the scale constant) the
-// planes are folded into the fp32 accumulator:
+// planes and a power-of-two scale per (row, 128-k chunk), constant over a scale
+// block of chunks.  Every digit plane goes through v_mfma_i32_32x32x32_i8 against
+// the raw int8 weights -- no weight conversion, exact int32 sums, one int32
+// accumulator per plane -- and at the end of a scale block the planes are folded
+// into the fp32 sums of the tile:
 //     acc += scale[b] * (65536 * float(top) + 256 * float(mid) + float(low)).
 // ND = 3 gives 23-bit activations (bf16 rounding of the LayerNorm and SwiGLU
 // outputs would otherwise dominate the error of a deep stack) for 1.5x the MFMA
@@ -22,16 +22,17 @@
 //   - weights are pre-tiled by pd_pack_* so that a wavefront's 16-byte-per-lane
 //     load is 1 KiB contiguous and is already an MFMA B operand:
 //     packed[(st*(K/32) + kb)*64 + lane] holds W[kb*32 + (lane/32)*16 + 0..15][st*32 + lane%32];
-//     each wave keeps PF units of its weight stream in flight in registers;
+//     each wave keeps R units of its weight stream in flight in registers;
 //   - activations (and their scales) are shared by the 4 waves through LDS.
 // A = activations (M = batch row), B = weights (N = output channel).
 //
 // Work split (deterministic stream-K).  The matrix is cut into units = (tile of
 // 128*NS columns, 128-k chunk), ordered tile-major; workgroup g of G takes the
-// contiguous range [g*U/G, (g+1)*U/G).  All workgroups stream the same number of
-// bytes (+-1 unit), whatever the matrix shape.  A tile covered by several
-// workgroups gets one partial per workgroup, in slot (g - first g of the tile);
-// consumers add the slots in index order, so results do not depend on timing.
+// contiguous range [g*U/G, (g+1)*U/G) (rounded to the ring depth).  All workgroups
+// stream the same number of bytes (+-1 unit), whatever the matrix shape.  A tile
+// covered by several workgroups gets one partial per workgroup, in slot (g - first
+// g of the tile); consumers add the slots in index order, so results do not depend
+// on timing.
 #include <stdlib.h>
 
 #include "common.h"
@@ -58,10 +59,10 @@ __device__ long long pd_dbg[4096 * 8];
 #endif
 
 // BM: 32-row batch blocks held in accumulators; NS: 32-column subtiles per wave;
-// R: weight units per wave held in a register ring.  grid = (G workgroups, row
-// groups of 32*BM rows).  Two workgroups share a compute unit (256 VGPRs per
-// wave, under 80 KiB of LDS each): every step ends in a workgroup barrier, and
-// it is the other workgroup's MFMAs that fill the matrix pipe while one waits.
+// ND: digit planes; R: weight units per wave held in a register ring; AD: operand
+// reads run AD - 1 MFMA groups ahead.  grid = (G workgroups, row groups of 32*BM
+// rows).  One workgroup per compute unit, one wave per SIMD with all 512 registers:
+// 256 of them are AGPRs and hold the int32 tiles for the whole unit loop.
 //
 // Weights go HBM -> registers with non-temporal buffer loads (each is 1 KiB
 // contiguous per wave and already a B operand); the loop body is unrolled R
@@ -425,14 +426,11 @@ __global__ __launch_bounds__(NT) void qgemm_kernel(const uint4* __restrict__ wp,
     const long long dbg_t0 = dbg_last, dbg_w0 = wall_clock64();
     long long dbg_first = 0;
 #endif
-    // One iteration per segment: clear the accumulators, run the segment's units,
-    // turn the int32 sums into one scaled fp32 partial.  (A fold inside the unit loop
-    // would put VALU reads and writes of the accumulators on the loop's back edge and
-    // the register allocator would then keep all of them in VGPRs.)  The weight ring
-    // and the activation stages run on across a segment end as long as the segment
-    // was a whole number of turns of the ring -- which the plan arranges for the
-    // decode shapes by starting workgroup ranges at multiples of R; otherwise the
-    // pipeline is filled again.
+    // A segment = the run of units of one scale block inside this range: clear the
+    // int32 accumulators, run its units, fold the int32 sums into the fp32 sums of the
+    // tile.  (A fold inside the unit loop would put VALU reads and writes of the
+    // accumulators on the loop's back edge and the register allocator would then keep
+    // all of them in VGPRs.)
     // byte offsets of the LDS stages: being read, published by the last barrier,
     // being written; they rotate every step
     unsigned char* const ldsb = &lds[0][0];
