@@ -459,28 +459,23 @@ __global__ __launch_bounds__(NT) void qgemm_kernel(const uint4* __restrict__ wp,
     while (!done) {
         done = true;
 
-            // fill: activations of the first two units straight into stages 0 and 1,
-            // those of the third into register stage 1 (step 0 writes them to stage 2),
-            // R weight units in flight, first operand reads of step 0.  (The weights are
-            // fetched after the wait for the first activations, not before: waiting for a
-            // younger load completes every older one, and the compiler would carry that
-            // into the wait counts at the head of the unit loop and drain the ring there.)
+            // fill: R weight units in flight (first: they come from HBM and take longest),
+            // activations of the first two units straight into stages 0 and 1, those of the
+            // third into register stage 1 (step 0 writes them to stage 2), first operand
+            // reads of step 0
             t_w = t_cur; c_w = c_cur; c_a = c_cur;
             u_w = u; u_a = u;
             a_so = (uint32_t)c_cur * (ND * KC);
             s_so = (uint32_t)c_cur * (QSCALE_ROWS * 4);
             PD_W_PTRS()
-            PD_A_NOW(0)
-            PD_LOAD_A(1)
-            PD_STORE_A(0, 0)
-            PD_STORE_A(STAGE, 1)
             PD_FETCH_W(0)
             PD_FETCH_W(1)
             if constexpr (R > 2) { PD_FETCH_W(2) }
             if constexpr (R > 3) { PD_FETCH_W(3) }
-            // (issued after the weights so that, as in the loop, every weight load has
-            // these behind it: the compiler's wait counts at the loop head take the
-            // smaller of the two paths)
+            PD_A_NOW(0)
+            PD_LOAD_A(1)
+            PD_STORE_A(0, 0)
+            PD_STORE_A(STAGE, 1)
             PD_LOAD_A(1)
             // Everything fetched so far is waited for here, once, so that the compiler's
             // wait counts at the head of the unit loop come from the loop's own back edge

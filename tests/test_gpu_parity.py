@@ -285,6 +285,23 @@ def test_decode_step_62b_shaped_sampled_rows(pd):
     assert scaled <= MAX_SCALED and rel <= REL_L2, (scaled, rel)
 
 
+def test_decode_step_540b_shard_shaped_layers(pd):
+    # layer shape of one eighth of the 540B model under 1D weight-stationary partitioning
+    # (Section 3.2.1: 6 of 48 heads, 9216 of 73728 FFN columns, full d_model 18432),
+    # batch 32, KV length 2048; 2 of the 118 layers, the shard's contribution chained locally
+    w = WORKLOADS["c4_540b_shard8"].with_(n_layers=2, name="c4_540b_shard8[2 layers]")
+    st, scaled, rel, _, _ = run_stack_parity(pd, w, rows=[0, 31, 13])
+    assert scaled <= MAX_SCALED and rel <= REL_L2, (scaled, rel)
+
+
+def test_decode_step_62b_long_context_shaped_layer(pd):
+    # batch 256 (four 64-row groups in the projections), KV capacity 8192 with ragged
+    # lengths in [4096, 8192) (many KV splits per row, ragged last blocks); 1 of the 64 layers
+    w = WORKLOADS["c5_62b_long"].with_(n_layers=1, name="c5_62b_long[1 layer]")
+    st, scaled, rel, _, _ = run_stack_parity(pd, w, rows=[0, 255, 64, 129, 7])
+    assert scaled <= MAX_SCALED and rel <= REL_L2, (scaled, rel)
+
+
 # ----------------------------------------------------- errors, graph replay ---
 
 def test_out_of_range_position_is_flagged_and_skipped(pd):
