@@ -188,6 +188,22 @@ pd_status pd_check_async(pd_handle* h, void* workspace, void* stream);
  *   The activations are converted to the library's 3-digit block fixed point
  *   (23 bits relative to each 128-element chunk's maximum) before the product. */
 pd_status pd_qgemm_workspace_bytes(int32_t B, int32_t K, int32_t N, int32_t workgroups, size_t* bytes);
+
+/* Host only (no GPU work): the deterministic work split of a [K][N] projection for
+ * batch B over `workgroups` workgroups (0 = automatic), as the kernels use it
+ * (Section 3.4's fused projections are the two instances).  Units = (column tile,
+ * 128-row chunk of K), tile-major; workgroup g owns units [range_begin[g],
+ * range_begin[g + 1]); the part of a tile inside one range is one partial-sum slot.
+ *   counts[5] (host, required) = { workgroups used G, tiles T, chunks per tile C,
+ *                                  padded rows of a partial slot, most slots in a tile }
+ *   range_begin (host, optional) >= G + 1 entries;  first_slot (host, optional) >= G
+ *   entries: slot index of range g inside its first tile;  slots_per_tile (host,
+ *   optional) >= T entries.  Call once with the optional arrays NULL to size them.
+ * c_split / blk0 / blk1: scale blocks of the operand (chunks [0, c_split) in blocks
+ * of blk0, the rest in blocks of blk1); they decide how ranges are aligned. */
+pd_status pd_qgemm_plan(int32_t B, int32_t K, int32_t N, int32_t workgroups, int32_t c_split,
+                        int32_t blk0, int32_t blk1, int32_t* counts, int64_t* range_begin,
+                        int32_t* first_slot, int32_t* slots_per_tile);
 pd_status pd_qgemm(const void* packed_w, const float* scale, const uint16_t* a, int32_t B,
                    int32_t K, int32_t N, float* out, int32_t workgroups, void* workspace,
                    size_t workspace_bytes, void* stream);

@@ -23,7 +23,7 @@ EXPORTS = [
     "pd_status_string", "pd_last_error", "pd_packed_layer_bytes", "pd_kv_cache_bytes",
     "pd_workspace_bytes", "pd_create", "pd_destroy", "pd_set_option", "pd_pack_layer",
     "pd_pack_matrix", "pd_kv_import", "pd_kv_export", "pd_decode_step", "pd_decode_layer",
-    "pd_check_async", "pd_qgemm_workspace_bytes", "pd_qgemm", "pd_mqa_attend",
+    "pd_check_async", "pd_qgemm_workspace_bytes", "pd_qgemm_plan", "pd_qgemm", "pd_mqa_attend",
     "pd_graph_capture", "pd_graph_replay", "pd_graph_release", "pd_profile_read",
 ]
 
@@ -104,6 +104,20 @@ def qgemm_workspace_bytes(B: int, K: int, N: int, workgroups: int = 0) -> int:
     _check(lib().pd_qgemm_workspace_bytes(ctypes.c_int32(B), ctypes.c_int32(K), ctypes.c_int32(N),
                                           ctypes.c_int32(workgroups), ctypes.byref(n)))
     return n.value
+
+
+def qgemm_plan(B: int, K: int, N: int, workgroups: int = 0, c_split: int = 0, blk0: int = 1, blk1: int = 1):
+    """Host only: (counts dict, range_begin list, first_slot list, slots_per_tile list)."""
+    counts = (ctypes.c_int32 * 5)()
+    args = [ctypes.c_int32(v) for v in (B, K, N, workgroups, c_split, blk0, blk1)]
+    _check(lib().pd_qgemm_plan(*args, counts, None, None, None))
+    G, T = counts[0], counts[1]
+    rb = (ctypes.c_int64 * (G + 1))()
+    fs = (ctypes.c_int32 * G)()
+    spt = (ctypes.c_int32 * T)()
+    _check(lib().pd_qgemm_plan(*args, counts, rb, fs, spt))
+    names = ("workgroups", "tiles", "chunks_per_tile", "rows", "max_slots")
+    return dict(zip(names, list(counts))), list(rb), list(fs), list(spt)
 
 
 def pack_matrix(w: torch.Tensor, packed: torch.Tensor, stream=None) -> None:

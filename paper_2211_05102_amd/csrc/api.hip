@@ -103,8 +103,15 @@ GemmPlans gemm_plans(const Shape& s, int B, int g_in_opt, int g_out_opt) {
     const int blk_ln = c_in < 1024 ? c_in : 1024;
     p.blk_o = c_attn < 16 ? c_attn : 16;
     p.blk_a = c_ffn < 16 ? c_ffn : 16;
-    p.in = pd::qgemm_plan(B, s.d, s.n_in, g_in_opt > 0 ? g_in_opt : PD_GEMM_WORKGROUPS, 0, 1, blk_ln, &p.slots_in);
-    p.out = pd::qgemm_plan(B, s.k_out, s.d, g_out_opt > 0 ? g_out_opt : PD_GEMM_WORKGROUPS, c_attn, p.blk_o,
+    // More than 64 rows: the projection runs one workgroup grid per 64-row group.  All
+    // groups together fill the chip once, and the workgroups that stream the same weight
+    // range (same x, different row group) are a multiple of 8 apart in launch order, i.e.
+    // on the same XCD, where all but the first find the weights in that XCD's L2.
+    const int row_groups = B > 32 ? (B + 63) / 64 : 1;
+    int g_auto = PD_GEMM_WORKGROUPS / row_groups;
+    if (row_groups > 1) g_auto = g_auto / 8 * 8;
+    p.in = pd::qgemm_plan(B, s.d, s.n_in, g_in_opt > 0 ? g_in_opt : g_auto, 0, 1, blk_ln, &p.slots_in);
+    p.out = pd::qgemm_plan(B, s.k_out, s.d, g_out_opt > 0 ? g_out_opt : g_auto, c_attn, p.blk_o,
                            p.blk_a, &p.slots_out);
     return p;
 }
@@ -526,6 +533,32 @@ pd_status pd_qgemm_workspace_bytes(int32_t B, int32_t K, int32_t N, int32_t work
     if (B < 1 || B > 256 || K < 128 || K % 128 || N < 32 || N % 32) return fail(PD_ERR_SHAPE, "unsupported GEMM shape");
     if (workgroups < 0 || workgroups > 4096) return fail(PD_ERR_RANGE, "workgroups out of range");
     *bytes = qgemm_ws(B, K, N, workgroups).total;
+    return PD_OK;
+}
+
+pd_status pd_qgemm_plan(int32_t B, int32_t K, int32_t N, int32_t workgroups, int32_t c_split,
+                        int32_t blk0, int32_t blk1, int32_t* counts, int64_t* range_begin,
+                        int32_t* first_slot, int32_t* slots_per_tile) {
+    if (!counts) return fail(PD_ERR_NULL, "counts is NULL");
+    if (B < 1 || B > 256 || K < 128 || K % 128 || N < 32 || N % 32) return fail(PD_ERR_SHAPE, "unsupported GEMM shape");
+    if (workgroups < 0 || workgroups > 4096) return fail(PD_ERR_RANGE, "workgroups out of range");
+    if (c_split < 0 || c_split > K / 128 || blk0 < 1 || blk0 > 1024 || blk1 < 1 || blk1 > 1024)
+        return fail(PD_ERR_RANGE, "scale blocks out of range");
+    int slots = 1;
+    const pd::SkqPlan pl = pd::qgemm_plan(B, K, N, workgroups > 0 ? workgroups : PD_GEMM_WORKGROUPS, c_split, blk0, blk1, &slots);
+    counts[0] = pl.G; counts[1] = pl.T; counts[2] = pl.C; counts[3] = pl.rows; counts[4] = slots;
+    const long long U = (long long)pl.T * pl.C;
+    for (int g = 0; g <= pl.G; g++) {
+        const long long u0 = pd::skq_begin(g, U, pl.G, pl.align);
+        if (range_begin) range_begin[g] = u0;
+        if (first_slot && g < pl.G) {
+            const int t0 = (int)(u0 / pl.C);
+            first_slot[g] = u0 < pd::skq_begin(g + 1, U, pl.G, pl.align)
+                                ? pd::skq_segments_upto(t0, (int)(u0 - (long long)t0 * pl.C), pl) : 0;
+        }
+    }
+    if (slots_per_tile)
+        for (int t = 0; t < pl.T; t++) slots_per_tile[t] = pd::skq_segments(t, pl);
     return PD_OK;
 }
 

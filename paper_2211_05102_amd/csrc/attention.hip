@@ -415,6 +415,7 @@ hipError_t launch_mqa_attend(const float* q, const void* kc_layer, const void* v
 #define PD_COMB(K) K<<<cgrid, block, 0, stream>>>(opart, ml, positions, H, dh, L_ctx, bps, nsplit, o, aq, acts, k_out, blk_o, nd)
     if (nsplit <= 4) PD_COMB(mqa_combine_kernel<4>);
     else if (nsplit <= 8) PD_COMB(mqa_combine_kernel<8>);
+    else if (nsplit <= 16) PD_COMB(mqa_combine_kernel<16>);
     else PD_COMB(mqa_combine_any_kernel);
 #undef PD_COMB
     return hipGetLastError();

@@ -706,8 +706,6 @@ hipError_t launch_qgemm(const void* wp, const void* qa, const float* scale_t, fl
     const int ring = ring_env ? atoi(ring_env) : 0;
     if (bm == 1) PD_LAUNCH(1, 2, 4, 4);
     else if (ring == 4) PD_LAUNCH(2, 2, 4, 3);
-    else if (ring == 5) PD_LAUNCH(2, 2, 2, 5);
-    else if (ring == 3) PD_LAUNCH(2, 2, 2, 3);
     else PD_LAUNCH(2, 2, 2, 4);
 #undef PD_LAUNCH
     return hipGetLastError();

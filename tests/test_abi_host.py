@@ -95,3 +95,48 @@ def test_argument_errors_come_before_any_launch(binding):
     dec.set_option("gemm_workgroups_in", 0)
     assert L.pd_status_string(i32(-7)).decode().startswith("position")
     dec.close()
+
+
+# ---- host logic: the deterministic work split of the projections ----------------
+
+@pytest.mark.parametrize("B,K,N,wg,c_split,blk0,blk1", [
+    (64, 8192, 74240, 0, 0, 1, 64),        # 62B-shaped input projection (one scale block per row)
+    (64, 40960, 8192, 0, 64, 16, 16),      # 62B-shaped output projection
+    (32, 18432, 20480, 0, 0, 1, 144),      # 540B-shard input projection
+    (256, 8192, 74240, 64, 0, 1, 64),      # four row groups
+    (8, 1280, 256, 3, 0, 1, 1), (1, 128, 32, 1, 0, 1, 1), (33, 512, 96, 2, 0, 1, 1),
+    (64, 4096, 544, 0, 0, 1, 1), (5, 384, 1000 // 32 * 32, 7, 1, 1, 2), (64, 40960, 256, 16, 64, 16, 16),
+    (130, 384, 320, 4096, 0, 1, 1),
+])
+def test_projection_work_split_covers_every_unit_once(binding, B, K, N, wg, c_split, blk0, blk1):
+    counts, begin, first_slot, slots = binding.qgemm_plan(B, K, N, wg, c_split, blk0, blk1)
+    G, T, C = counts["workgroups"], counts["tiles"], counts["chunks_per_tile"]
+    U = T * C
+    assert C == K // 128 and T == -(-N // 256) and 1 <= G <= max(1, min(wg or 256, U))
+    assert counts["rows"] % 32 == 0 and counts["rows"] >= B and counts["rows"] - B < 64
+    # ranges: contiguous, ordered, cover [0, U) exactly once, balanced to within the alignment
+    assert begin[0] == 0 and begin[G] == U and all(begin[g] <= begin[g + 1] for g in range(G))
+    sizes = [begin[g + 1] - begin[g] for g in range(G)]
+    assert max(sizes) - min(sizes) <= 8
+    # slots: brute force over the ranges -- a tile has one slot per range that holds one of its
+    # units, numbered in range order; first_slot[g] is range g's number in the tile it starts in
+    per_tile = [0] * T
+    for g in range(G):
+        if begin[g] == begin[g + 1]:
+            continue
+        t_first, t_last = begin[g] // C, (begin[g + 1] - 1) // C
+        assert first_slot[g] == per_tile[t_first], (g, first_slot[g], per_tile[t_first])
+        for t in range(t_first, t_last + 1):
+            per_tile[t] += 1
+    assert per_tile == slots and max(slots) == counts["max_slots"] and min(slots) >= 1
+
+
+def test_projection_work_split_rejects_bad_arguments(binding):
+    L = binding.lib()
+    import ctypes
+    counts = (ctypes.c_int32 * 5)()
+    i32 = ctypes.c_int32
+    assert L.pd_qgemm_plan(i32(8), i32(100), i32(32), i32(0), i32(0), i32(1), i32(1), counts, None, None, None) == binding.PD_ERR_SHAPE
+    assert L.pd_qgemm_plan(i32(8), i32(128), i32(32), i32(5000), i32(0), i32(1), i32(1), counts, None, None, None) == binding.PD_ERR_RANGE
+    assert L.pd_qgemm_plan(i32(8), i32(128), i32(32), i32(0), i32(2), i32(1), i32(1), counts, None, None, None) == binding.PD_ERR_RANGE
+    assert L.pd_qgemm_plan(i32(8), i32(128), i32(32), i32(0), i32(0), i32(1), i32(1), None, None, None, None) == binding.PD_ERR_NULL
