@@ -33,8 +33,6 @@
 // covered by several workgroups gets one partial per workgroup, in slot (g - first
 // g of the tile); consumers add the slots in index order, so results do not depend
 // on timing.
-#include <stdlib.h>
-
 #include "common.h"
 #include "kernels.h"
 
@@ -702,10 +700,7 @@ hipError_t launch_qgemm(const void* wp, const void* qa, const float* scale_t, fl
     if ((long long)B * K * nd >= (1ll << 31) || (long long)K * N >= (1ll << 32)) return hipErrorInvalidValue;
     if ((long long)pl.T * pl.C >= (1ll << 31)) return hipErrorInvalidValue;
     if ((long long)pl.max_slots * pl.rows * N * 4 >= (1ll << 32)) return hipErrorInvalidValue;
-    const char* ring_env = getenv("PD_GEMM_RING");  // tuning only
-    const int ring = ring_env ? atoi(ring_env) : 0;
     if (bm == 1) PD_LAUNCH(1, 2, 4, 4);
-    else if (ring == 4) PD_LAUNCH(2, 2, 4, 3);
     else PD_LAUNCH(2, 2, 2, 4);
 #undef PD_LAUNCH
     return hipGetLastError();
