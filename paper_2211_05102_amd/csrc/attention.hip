@@ -33,6 +33,13 @@
 
 namespace pd {
 
+#ifdef PD_DBG_TIMING
+__device__ long long pd_dbg_att[4096 * 8];
+#define PD_AT(x) const long long x = clock64();
+#else
+#define PD_AT(x)
+#endif
+
 // o[b][h*dh + c] = sum_s w_s O_s[c] / sum_s w_s l_s,  w_s = 2^(m_s - max m), splits in index order.
 // One workgroup per scale block of the row (blk_o chunks of 128 elements, at most
 // 16); each wave takes every fourth chunk, two adjacent channels per lane.  The
@@ -172,13 +179,16 @@ __global__ __launch_bounds__(256) void mqa_attend_kernel(
     constexpr int DB = DH / 32;  // 32-channel blocks of the output
     constexpr int BLK_U4 = 4 * DH;  // uint4 per 32-token block (K and V alike)
     __shared__ float ml_s[4][64][2];
-    // q operands [plane][j][lane] during the block loop, then the merge buffer [DB*16][64] floats
-    __shared__ uint4 smem[2 * KJ * 64];
-    static_assert(sizeof(uint4) * 2 * KJ * 64 >= sizeof(float) * DB * 16 * 64, "merge buffer fits");
-    float (*obuf)[64] = reinterpret_cast<float (*)[64]>(smem);
+    // q operands [plane][j][lane] during the block loop, then the merge buffer [DB][3][4][64] of f32x4
+    constexpr int SMEM_U4 = 2 * KJ * 64 > DB * 3 * 4 * 64 ? 2 * KJ * 64 : DB * 3 * 4 * 64;
+    __shared__ uint4 smem[SMEM_U4];
 
+    PD_AT(ta0)
     const int b = blockIdx.y, split = blockIdx.x;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    // (uniform by construction; saying so keeps the buffer offsets derived from it scalar --
+    // otherwise every load below is wrapped in a loop over the "distinct" values)
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int g = lane >> 5, l32 = lane & 31;
     const int P = positions[b];
     if (P < 0 || P >= L_ctx) return;  // reported by the prep kernel; nothing is read or written
@@ -187,25 +197,6 @@ __global__ __launch_bounds__(256) void mqa_attend_kernel(
     const int blk1 = blk0 + bps < nblk ? blk0 + bps : nblk;
     if (blk0 >= blk1) return;
     const int nblk_cap = L_ctx >> 5;
-
-    // q operand (B matrix): slot (j, lane = (head, g)) holds q[h][16j + 8g .. +8) * log2(e)/sqrt(dh),
-    // split into bf16 hi (plane 0) and lo (plane 1).  Padded heads duplicate the last one.
-    for (int slot = tid; slot < KJ * 64; slot += 256) {
-        const int j = slot >> 6, ln = slot & 63;
-        const int hh = (ln & 31) < H ? (ln & 31) : H - 1;
-        const float* src = q + ((size_t)b * H + hh) * DH + 16 * j + 8 * (ln >> 5);
-        const f32x4 a0 = *reinterpret_cast<const f32x4*>(src) * scale_log2e;
-        const f32x4 a1 = *reinterpret_cast<const f32x4*>(src + 4) * scale_log2e;
-        const uint4 hi = {pack_bf16x2(a0.x, a0.y), pack_bf16x2(a0.z, a0.w), pack_bf16x2(a1.x, a1.y),
-                          pack_bf16x2(a1.z, a1.w)};
-        const uint4 lo = {pack_bf16x2(a0.x - bf16_lo(hi.x), a0.y - bf16_hi(hi.x)),
-                          pack_bf16x2(a0.z - bf16_lo(hi.y), a0.w - bf16_hi(hi.y)),
-                          pack_bf16x2(a1.x - bf16_lo(hi.z), a1.y - bf16_hi(hi.z)),
-                          pack_bf16x2(a1.z - bf16_lo(hi.w), a1.w - bf16_hi(hi.w))};
-        smem[slot] = hi;
-        smem[KJ * 64 + slot] = lo;
-    }
-    __syncthreads();
 
     // K and V of this sequence as buffers that end where this workgroup's share
     // ends: the software pipeline below always asks for the next block, and a read
@@ -223,15 +214,51 @@ __global__ __launch_bounds__(256) void mqa_attend_kernel(
 #pragma unroll
         for (int r = 0; r < 16; r++) O[db][r] = 0.f;
 
-    // One ring of KJ 1-KiB pieces per wave, always full: the K pieces of a block are
-    // consumed in order and each slot is refilled at once with the V piece of the
-    // same index; the V pieces are consumed in order and refilled with the K pieces
-    // of this wave's next block.  Non-temporal: every byte is used once.
+    // Two rings of KJ 1-KiB pieces per wave, always full: the K pieces of a block are
+    // consumed in order and each slot is refilled at once with the same piece of this
+    // wave's next block; likewise the V pieces.  A whole block ahead (32 KiB per wave,
+    // 128 KiB per compute unit) stays in flight.  Non-temporal: every byte is used once.
+    // q of this row first (vector-memory operations complete in order: the wait for these
+    // few loads must not include the K and V blocks requested after them)
+    constexpr int QIT = (KJ * 64 + 255) / 256;
+    f32x4 qa0[QIT], qa1[QIT];
+#pragma unroll
+    for (int it = 0; it < QIT; it++) {
+        int slot = it * 256 + tid;
+        slot = slot < KJ * 64 ? slot : KJ * 64 - 1;
+        const int j = slot >> 6, ln = slot & 63;
+        const int hh = (ln & 31) < H ? (ln & 31) : H - 1;
+        const float* src = q + ((size_t)b * H + hh) * DH + 16 * j + 8 * (ln >> 5);
+        qa0[it] = *reinterpret_cast<const f32x4*>(src);
+        qa1[it] = *reinterpret_cast<const f32x4*>(src + 4);
+    }
+    __builtin_amdgcn_sched_barrier(0);
     u32x4 ring[KJ];
     const int first = blk0 + wave;
 #pragma unroll
     for (int j = 0; j < KJ; j++)
         ring[j] = __builtin_amdgcn_raw_buffer_load_b128(k_rs, lane16, (first * BLK_U4 + j * 64) * 16, 2);
+
+    // (staged while the first K and V blocks are on their way from HBM)
+    // q operand (B matrix): slot (j, lane = (head, g)) holds q[h][16j + 8g .. +8) * log2(e)/sqrt(dh),
+    // split into bf16 hi (plane 0) and lo (plane 1).  Padded heads duplicate the last one.
+#pragma unroll
+    for (int it = 0; it < QIT; it++) {
+        const int slot = it * 256 + tid;
+        const f32x4 a0 = qa0[it] * scale_log2e, a1 = qa1[it] * scale_log2e;
+        const uint4 hi = {pack_bf16x2(a0.x, a0.y), pack_bf16x2(a0.z, a0.w), pack_bf16x2(a1.x, a1.y),
+                          pack_bf16x2(a1.z, a1.w)};
+        const uint4 lo = {pack_bf16x2(a0.x - bf16_lo(hi.x), a0.y - bf16_hi(hi.x)),
+                          pack_bf16x2(a0.z - bf16_lo(hi.y), a0.w - bf16_hi(hi.y)),
+                          pack_bf16x2(a1.x - bf16_lo(hi.z), a1.y - bf16_hi(hi.z)),
+                          pack_bf16x2(a1.z - bf16_lo(hi.w), a1.w - bf16_hi(hi.w))};
+        if (slot < KJ * 64) {
+            smem[slot] = hi;
+            smem[KJ * 64 + slot] = lo;
+        }
+    }
+    __syncthreads();
+    PD_AT(ta1)
 
     for (int blk = first; blk < blk1; blk += 4) {
         const int blk_off = blk * BLK_U4 * 16, next_off = (blk + 4) * BLK_U4 * 16;
@@ -270,10 +297,20 @@ __global__ __launch_bounds__(256) void mqa_attend_kernel(
         l_run = l_run * alpha + psum;
         m_run = m_new;
         if (__any(alpha != 1.f)) {
+            // The output accumulators stay in AGPRs for the whole loop (that is what leaves
+            // room for the second ring in the vector registers); this rare rescale reads
+            // each value out, scales it and writes it back explicitly.  The trailing no-ops
+            // cover the wait states between an AGPR write and the MFMA that reads it.
 #pragma unroll
             for (int db = 0; db < DB; db++)
 #pragma unroll
-                for (int r = 0; r < 16; r++) O[db][r] *= alpha;
+                for (int r = 0; r < 16; r++) {
+                    float t_;
+                    asm volatile("v_accvgpr_read_b32 %1, %0\n\tv_mul_f32 %1, %1, %2\n\tv_accvgpr_write_b32 %0, %1"
+                                 : "+a"(O[db][r]), "=&v"(t_)
+                                 : "v"(alpha));
+                }
+            asm volatile("s_nop 4");
         }
         bf16x8 pop[2][2];  // [kk][hi, lo]
 #pragma unroll
@@ -310,9 +347,14 @@ __global__ __launch_bounds__(256) void mqa_attend_kernel(
                     __builtin_amdgcn_raw_buffer_load_b128(k_rs, lane16, next_off + (db * 2 + kk) * 1024, 2);
             }
     }
+    PD_AT(ta2)
     __syncthreads();  // every wave is done with the q operands: smem becomes the merge buffer
+    PD_AT(ta3)
 
-    // ---- merge the 4 waves (a wave without blocks has m = -inf, l = 0, O = 0)
+    // ---- merge the 4 waves (a wave without blocks has m = -inf, l = 0, O = 0).  Output
+    // block db belongs to wave db % 4: every wave leaves its scaled sums of the blocks it
+    // does not own in LDS (one exchange, all waves at once), the owner adds the three
+    // contributions to its own in wave order and stores its share of the partial.
     float l_tot = l_run + __shfl_xor(l_run, 32, 64);
     ml_s[wave][lane][0] = m_run;
     ml_s[wave][lane][1] = l_tot;
@@ -320,47 +362,65 @@ __global__ __launch_bounds__(256) void mqa_attend_kernel(
     float m_all = fmaxf(fmaxf(ml_s[0][lane][0], ml_s[1][lane][0]),
                         fmaxf(ml_s[2][lane][0], ml_s[3][lane][0]));  // finite: wave 0 had a block
     const float f_own = __builtin_amdgcn_exp2f(m_run - m_all);
+    f32x4 (*mbuf)[3][4][64] = reinterpret_cast<f32x4 (*)[3][4][64]>(smem);  // [db][source][i][lane]
 #pragma unroll
-    for (int db = 0; db < DB; db++)
+    for (int db = 0; db < DB; db++) {
 #pragma unroll
         for (int r = 0; r < 16; r++) O[db][r] *= f_own;
-    for (int w = 1; w < 4; w++) {
-        if (wave == w) {
+        const int src = (wave - (db & 3) - 1) & 3;  // 0..2 for the three waves that do not own db
+        if ((db & 3) != wave) {
 #pragma unroll
-            for (int db = 0; db < DB; db++)
-#pragma unroll
-                for (int r = 0; r < 16; r++) obuf[db * 16 + r][lane] = O[db][r];
+            for (int i = 0; i < 4; i++)
+                mbuf[db][src][i][lane] = (f32x4){O[db][4 * i], O[db][4 * i + 1], O[db][4 * i + 2], O[db][4 * i + 3]};
         }
-        __syncthreads();
-        if (wave == 0) {
-#pragma unroll
-            for (int db = 0; db < DB; db++)
-#pragma unroll
-                for (int r = 0; r < 16; r++) O[db][r] += obuf[db * 16 + r][lane];
-        }
-        __syncthreads();
     }
-    if (wave == 0 && l32 < H) {
+    __syncthreads();
+    const size_t row = ((size_t)b * nsplit + split) * H + l32;
+    if (wave == 0 && l32 < H && g == 0) {
         float l_all = 0.f;
 #pragma unroll
         for (int w = 0; w < 4; w++)
             l_all += ml_s[w][lane][1] * __builtin_amdgcn_exp2f(ml_s[w][lane][0] - m_all);
-        const size_t row = ((size_t)b * nsplit + split) * H + l32;
-        if (g == 0) {
-            ml[row * 2 + 0] = m_all;
-            ml[row * 2 + 1] = l_all;
-        }
-        float* orow = opart + row * DH;
-#pragma unroll
-        for (int db = 0; db < DB; db++)
-#pragma unroll
-            for (int i = 0; i < 4; i++) {
-                f32x4 v = {O[db][4 * i + 0], O[db][4 * i + 1], O[db][4 * i + 2], O[db][4 * i + 3]};
-                *reinterpret_cast<f32x4*>(orow + db * 32 + 8 * i + 4 * g) = v;
-            }
+        ml[row * 2 + 0] = m_all;
+        ml[row * 2 + 1] = l_all;
     }
-
+    float* orow = opart + row * DH;
+#pragma unroll
+    for (int db = 0; db < DB; db++) {
+        if ((db & 3) != wave) continue;
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+            f32x4 v = {O[db][4 * i + 0], O[db][4 * i + 1], O[db][4 * i + 2], O[db][4 * i + 3]};
+            // contributions in wave order (fixed summation order): sources (wave+1, wave+2, wave+3) % 4
+            f32x4 c[3];
+#pragma unroll
+            for (int k = 0; k < 3; k++) c[k] = mbuf[db][k][i][lane];
+            // source index k is wave (owner + 1 + k) % 4; add own and the others by ascending wave
+            f32x4 sum = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int w = 0; w < 4; w++) {
+                const int k = (w - wave - 1) & 3;
+                sum += (w == wave) ? v : c[k < 3 ? k : 0];
+            }
+            if (l32 < H) *reinterpret_cast<f32x4*>(orow + db * 32 + 8 * i + 4 * g) = sum;
+        }
+    }
+#ifdef PD_DBG_TIMING
+    PD_AT(ta4)
+    if (lane == 0) {
+        long long* d_ = pd_dbg_att + ((blockIdx.y * gridDim.x + blockIdx.x) * 4 + wave) * 8;
+        if ((blockIdx.y * gridDim.x + blockIdx.x) * 4 + wave < 4096) {
+            d_[0] = ta1 - ta0; d_[1] = ta2 - ta1; d_[2] = ta3 - ta2; d_[3] = ta4 - ta3; d_[4] = wall_clock64();
+        }
+    }
+#endif
 }
+
+#ifdef PD_DBG_TIMING
+extern "C" int pd_dbg_read_att(long long* host, int n) {
+    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(pd_dbg_att), sizeof(long long) * n);
+}
+#endif
 
 // canonical [B][L_ctx][dh]  <->  library block layout, one element per thread
 __global__ __launch_bounds__(256) void kv_convert_kernel(const uint16_t* __restrict__ src,
