@@ -244,6 +244,34 @@ def test_decode_step_small_shapes(pd, shape):
     assert scaled <= MAX_SCALED and rel <= REL_L2, (scaled, rel)
 
 
+def _random_shapes(n, seed):
+    rng = np.random.default_rng(seed)
+    shapes = []
+    for _ in range(n):
+        dh = int(rng.choice([64, 128, 256]))
+        H = int(rng.integers(1, 33))
+        if dh == 64 and H % 2:
+            H += 1  # n_heads * d_head must be a multiple of 128 (one chunk of the projection operand)
+        d = 128 * int(rng.integers(1, 9))
+        F = 128 * int(rng.integers(1, 9))
+        B = int(rng.choice([1, 2, 7, 31, 32, 33, 64, 65, 97]))
+        L = 32 * int(rng.integers(1, 9))
+        layers = int(rng.integers(1, 4))
+        shapes.append((layers, d, H, dh, F, B, L))
+    return shapes
+
+
+@pytest.mark.parametrize("shape", _random_shapes(10, 20221109))
+def test_decode_step_random_small_shapes(pd, shape):
+    # seeded shapes that the named workloads do not reach: odd head counts (padded MFMA
+    # columns), all three head sizes, batches around the 32- and 64-row group sizes,
+    # ragged positions from 0 (a single live slot) to the last slot of the cache
+    L_, d, H, dh, F, B, L = shape
+    w = Workload("rand", L_, d, H, dh, F, B, L, positions="ragged", pos_lo=0, pos_hi=L)
+    st, scaled, rel, _, _ = run_stack_parity(pd, w, name=f"rand{shape}")
+    assert scaled <= MAX_SCALED and rel <= REL_L2, (scaled, rel)
+
+
 def test_decode_layer_partial_without_residual(pd):
     # a weight shard returns its unreduced contribution (Section 3.2.1)
     from paper_2211_05102_amd import harness
