@@ -104,7 +104,8 @@ pd_status pd_create(const pd_model_desc* desc, pd_handle** out);
 pd_status pd_destroy(pd_handle* h);
 /* Tuning knobs: "gemm_workgroups_in", "gemm_workgroups_out" (workgroups that
  * share the weight matrix of the input / output projection, 0 = automatic:
- * one per compute unit and 64-row group; values above 256 are rejected),
+ * at most one per compute unit and 64-row group, chosen so that the ranges come
+ * out even; values above 256 are rejected),
  * "attn_blocks_per_split" (32-token blocks per attention
  * workgroup, 0 = automatic), "act_digits" (2 or 3 int8 digit planes per
  * projection operand), "profile_kernel" (see pd_profile_read).  Unknown names

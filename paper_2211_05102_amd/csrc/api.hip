@@ -110,9 +110,11 @@ GemmPlans gemm_plans(const Shape& s, int B, int g_in_opt, int g_out_opt) {
     const int row_groups = B > 32 ? (B + 63) / 64 : 1;
     int g_auto = PD_GEMM_WORKGROUPS / row_groups;
     if (row_groups > 1) g_auto = g_auto / 8 * 8;
-    p.in = pd::qgemm_plan(B, s.d, s.n_in, g_in_opt > 0 ? g_in_opt : g_auto, 0, 1, blk_ln, &p.slots_in);
-    p.out = pd::qgemm_plan(B, s.k_out, s.d, g_out_opt > 0 ? g_out_opt : g_auto, c_attn, p.blk_o,
-                           p.blk_a, &p.slots_out);
+    const int g_in = g_in_opt > 0 ? g_in_opt : pd::qgemm_auto_workgroups(B, s.d, s.n_in, g_auto, 0, 1, blk_ln);
+    const int g_out = g_out_opt > 0 ? g_out_opt
+                                    : pd::qgemm_auto_workgroups(B, s.k_out, s.d, g_auto, c_attn, p.blk_o, p.blk_a);
+    p.in = pd::qgemm_plan(B, s.d, s.n_in, g_in, 0, 1, blk_ln, &p.slots_in);
+    p.out = pd::qgemm_plan(B, s.k_out, s.d, g_out, c_attn, p.blk_o, p.blk_a, &p.slots_out);
     return p;
 }
 

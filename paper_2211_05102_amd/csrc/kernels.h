@@ -13,6 +13,7 @@ namespace pd {
 void qgemm_config(int B, int* bm, int* ns, int* tile_cols);
 SkqPlan qgemm_plan(int B, int K, int N, int workgroups, int c_split, int blk0, int blk1,
                    int* max_slots);
+int qgemm_auto_workgroups(int B, int K, int N, int g_max, int c_split, int blk0, int blk1);
 hipError_t launch_skq_table(SkqPlan pl, int* nseg, hipStream_t stream);
 hipError_t launch_qgemm(const void* wp, const void* qa, const float* scale_t, float* part, int B,
                         int K, int N, SkqPlan pl, int nd, hipStream_t stream);

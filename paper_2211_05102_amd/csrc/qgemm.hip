@@ -636,6 +636,9 @@ __global__ __launch_bounds__(256) void qgemm_reduce_kernel(const float* __restri
 
 // ---- host launchers -----------------------------------------------------------
 
+// weight units per wave kept in flight (the R of the kernel instance launch_qgemm picks)
+static int qgemm_ring(int bm) { return bm == 1 ? 4 : 2; }
+
 void qgemm_config(int B, int* bm, int* ns, int* tile_cols) {
     int blocks = (B + 31) / 32;
     *bm = blocks <= 1 ? 1 : 2;  // more than 64 rows: several row groups
@@ -655,9 +658,13 @@ SkqPlan qgemm_plan(int B, int K, int N, int workgroups, int c_split, int blk0, i
     pl.T = (N + tc - 1) / tc;
     const long long U = (long long)pl.T * pl.C;
     pl.G = (int)(workgroups < U ? (workgroups < 1 ? 1 : workgroups) : U);
-    // ranges that start at multiples of the weight ring (4 units) keep the pipeline of
-    // the unit loop running across segment ends; only worth it for ranges of many units
-    pl.align = (U / pl.G >= 16 && pl.C % 4 == 0 && c_split % 4 == 0 && (c_split == 0 || blk0 % 4 == 0) && blk1 % 4 == 0) ? 4 : 1;
+    // ranges that start at multiples of the weight ring (qgemm_ring() units) keep the
+    // pipeline of the unit loop running across segment ends; only worth it for ranges of
+    // many units.  (The ring is also the granularity of the split: ranges differ by at
+    // most one ring, which is what the slowest workgroup streams more than the others.)
+    const int ring = qgemm_ring(bm);
+    pl.align = (U / pl.G >= 16 && pl.C % ring == 0 && c_split % ring == 0 &&
+                (c_split == 0 || blk0 % ring == 0) && blk1 % ring == 0) ? ring : 1;
     pl.c_split = c_split;
     pl.blk0 = blk0;
     pl.blk1 = blk1;
@@ -671,6 +678,30 @@ SkqPlan qgemm_plan(int B, int K, int N, int workgroups, int c_split, int blk0, i
     pl.max_slots = mx;
     if (max_slots) *max_slots = mx;
     return pl;
+}
+
+// Automatic workgroup count: at most g_max, at least 7/8 of it, in steps of 8 (one per XCD),
+// whichever leaves the longest range shortest relative to an even split.  The kernel is
+// bandwidth-bound, so its time follows the longest range times the number of ranges that
+// share the bandwidth; a few idle compute units cost less than one ring of extra units on
+// the slowest workgroup (62B-shaped input projection: 232 ranges of 80 units beat 256 of
+// 72 or 74).
+int qgemm_auto_workgroups(int B, int K, int N, int g_max, int c_split, int blk0, int blk1) {
+    if (g_max < 16) return g_max < 1 ? 1 : g_max;
+    int best_g = g_max;
+    long long best_cost = -1;
+    for (int g = g_max; g >= g_max - g_max / 8; g -= 8) {
+        const SkqPlan pl = qgemm_plan(B, K, N, g, c_split, blk0, blk1, nullptr);
+        const long long U = (long long)pl.T * pl.C;
+        long long longest = 0;
+        for (int i = 0; i < pl.G; i++) {
+            const long long n = skq_begin(i + 1, U, pl.G, pl.align) - skq_begin(i, U, pl.G, pl.align);
+            if (n > longest) longest = n;
+        }
+        const long long cost = longest * pl.G;
+        if (best_cost < 0 || cost < best_cost) { best_cost = cost; best_g = g; }
+    }
+    return best_g;
 }
 
 hipError_t launch_skq_table(SkqPlan pl, int* nseg, hipStream_t stream) {
@@ -700,7 +731,7 @@ hipError_t launch_qgemm(const void* wp, const void* qa, const float* scale_t, fl
     if ((long long)B * K * nd >= (1ll << 31) || (long long)K * N >= (1ll << 32)) return hipErrorInvalidValue;
     if ((long long)pl.T * pl.C >= (1ll << 31)) return hipErrorInvalidValue;
     if ((long long)pl.max_slots * pl.rows * N * 4 >= (1ll << 32)) return hipErrorInvalidValue;
-    if (bm == 1) PD_LAUNCH(1, 2, 4, 4);
+    if (bm == 1) PD_LAUNCH(1, 2, 4, 4);  // rings as in qgemm_ring()
     else PD_LAUNCH(2, 2, 2, 4);
 #undef PD_LAUNCH
     return hipGetLastError();
