@@ -108,37 +108,12 @@ __global__ __launch_bounds__(NT) void qgemm_kernel(const uint4* __restrict__ wp,
     const int u0 = __builtin_amdgcn_readfirstlane(rec[0]);
     const int u1 = __builtin_amdgcn_readfirstlane(rec[1]);
     if (u0 >= u1) return;
-    const int row0 = blockIdx.y * ROWS;
 
-    // byte offsets (within one chunk column of the activation matrix) of the pieces
-    // this thread moves, and where they go in an LDS stage; rows >= B repeat row B-1
-    // (their results are never stored)
-    uint32_t aoff[APT], aslot[APT];
-#pragma unroll
-    for (int it = 0; it < APT; it++) {
-        int p_ = it * NT + tid;
-        p_ = p_ < ROWS * PPR ? p_ : ROWS * PPR - 1;
-        aslot[it] = (p_ / PPR) * PITCH + (p_ % PPR) * 16;
-        int rg = row0 + p_ / PPR;
-        rg = rg < B ? rg : B - 1;
-        aoff[it] = (uint32_t)rg * (uint32_t)(K * ND) + (p_ % PPR) * 16;
-    }
-    // (every thread moves a row scale: threads beyond the rows repeat the first ones)
-    int srow = row0 + (tid & (ROWS - 1));
-    srow = srow < B ? srow : B - 1;
-    const uint32_t srow4 = srow * 4, sslot = ROWS * PITCH + (tid & (ROWS - 1)) * 4;
     // Every global read is a buffer load: a scalar descriptor and a scalar byte
     // offset that moves with the unit, plus a per-lane offset that never changes --
     // no 64-bit address arithmetic in vector registers, and reads past the end of
     // a range return zero instead of faulting.
     const uint32_t lane16 = lane * 16;
-    const __amdgpu_buffer_rsrc_t a_rs = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<unsigned char*>(qa), 0, B * K * ND, 0x00020000);
-    const __amdgpu_buffer_rsrc_t s_rs = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<float*>(scale_t), 0, C * QSCALE_ROWS * 4, 0x00020000);
-    // partial sums: slots of pl.rows (whole row groups) x N, so stores need no row test
-    const __amdgpu_buffer_rsrc_t p_rs = __builtin_amdgcn_make_buffer_rsrc(
-        part, 0, (int)((uint32_t)pl.max_slots * (uint32_t)pl.rows * (uint32_t)N * 4u), 0x00020000);
     // One descriptor spans the whole packed matrix; the 32-column stream of subtile i
     // and the unit inside it are a scalar byte offset that advances by one unit per
     // step (a constant) and is recomputed only when the fetch moves to the next tile.
@@ -146,55 +121,12 @@ __global__ __launch_bounds__(NT) void qgemm_kernel(const uint4* __restrict__ wp,
         const_cast<unsigned char*>(reinterpret_cast<const unsigned char*>(wp)), 0,
         (int)((uint32_t)n_sub * (uint32_t)K * 32u), 0x00020000);
     uint32_t w_so[NS];
-#pragma unroll
-    for (int i = 0; i < NS; i++) w_so[i] = 0;
-    uint32_t a_so = 0, s_so = 0;  // byte offsets of chunk c_a in the activation and scale arrays
-
-    // The int32 accumulators live in the accumulation registers (AGPRs) for the whole
-    // loop.  They are cleared by an MFMA of zeros rather than by moves: the register
-    // allocator keeps a loop-carried tile in AGPRs only if every value that flows into
-    // it comes out of an MFMA; a single VALU-written zero makes it hold the tiles in
-    // VGPRs and copy all of them to and from AGPRs around every unit.
-    const i32x4 zero4 = {0, 0, 0, 0};
-    const i32x16 zero16 = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-    i32x16 iacc[ND][NS][BM];
-#pragma unroll
-    for (int p = 0; p < ND; p++)
-#pragma unroll
-        for (int i = 0; i < NS; i++)
-#pragma unroll
-            for (int bm = 0; bm < BM; bm++)
-                iacc[p][i][bm] = __builtin_amdgcn_mfma_i32_32x32x32_i8(zero4, zero4, zero16, 0, 0, 0);
-
-#pragma unroll
-    for (int j = 0; j < NS * BM * 4; j++) accl[j][tid] = (f32x4){0.f, 0.f, 0.f, 0.f};
-
-    u32x4 wreg[R][NS][KB];
-    u32x4 areg[2][APT];
-    float sreg[2] = {0.f, 0.f};
-    i32x4 aop[AD][BM];  // operand reads run AD - 1 groups ahead of their MFMAs
-
     // (tile, chunk) of the unit being computed; of the next weight unit to fetch
-    // (saturates at the last unit of the range); chunk of the next activation stage
+    // (saturates at the last unit of the range)
     int t_cur = __builtin_amdgcn_readfirstlane(rec[3]);
     int c_cur = u0 - t_cur * C;
-    int t_w = t_cur, c_w = c_cur, c_a = c_cur;
-    int u = u0, u_w = u0, u_a = u0;
-    int slot = __builtin_amdgcn_readfirstlane(rec[2]);  // partial slot of this range in tile t_cur
-
-    // end of the scale block that holds chunk c
-    auto block_end = [&](int c) {
-        int e;
-        if (c < c_split) {
-            e = (c / blk0 + 1) * blk0;
-            e = e < c_split ? e : c_split;
-        } else {
-            e = c_split + ((c - c_split) / blk1 + 1) * blk1;
-            e = e < C ? e : C;
-        }
-        return __builtin_amdgcn_readfirstlane(e);
-    };
-    int seg_end = block_end(c_cur);
+    int t_w = t_cur, c_w = c_cur, u_w = u0;
+    u32x4 wreg[R][NS][KB];
 
     // weight unit (t_w, c_w) -> ring slot s, one 32-k block at a time
 #define PD_W_PTRS()                                                                      \
@@ -229,6 +161,84 @@ __global__ __launch_bounds__(NT) void qgemm_kernel(const uint4* __restrict__ wp,
         _Pragma("unroll") for (int kb = 0; kb < KB; kb++) { PD_W_LOAD(s, kb) }           \
         PD_W_NEXT()                                                                      \
     }
+    // The first R weight units are requested before anything else is set up: they come
+    // from HBM and are what the first unit waits for longest.
+    PD_W_PTRS()
+    PD_FETCH_W(0)
+    PD_FETCH_W(1)
+    if constexpr (R > 2) { PD_FETCH_W(2) }
+    if constexpr (R > 3) { PD_FETCH_W(3) }
+    bool w_fetched = true;
+    __builtin_amdgcn_sched_barrier(0);
+
+    const int row0 = blockIdx.y * ROWS;
+
+    // byte offsets (within one chunk column of the activation matrix) of the pieces
+    // this thread moves, and where they go in an LDS stage; rows >= B repeat row B-1
+    // (their results are never stored)
+    uint32_t aoff[APT], aslot[APT];
+#pragma unroll
+    for (int it = 0; it < APT; it++) {
+        int p_ = it * NT + tid;
+        p_ = p_ < ROWS * PPR ? p_ : ROWS * PPR - 1;
+        aslot[it] = (p_ / PPR) * PITCH + (p_ % PPR) * 16;
+        int rg = row0 + p_ / PPR;
+        rg = rg < B ? rg : B - 1;
+        aoff[it] = (uint32_t)rg * (uint32_t)(K * ND) + (p_ % PPR) * 16;
+    }
+    // (every thread moves a row scale: threads beyond the rows repeat the first ones)
+    int srow = row0 + (tid & (ROWS - 1));
+    srow = srow < B ? srow : B - 1;
+    const uint32_t srow4 = srow * 4, sslot = ROWS * PITCH + (tid & (ROWS - 1)) * 4;
+    const __amdgpu_buffer_rsrc_t a_rs = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<unsigned char*>(qa), 0, B * K * ND, 0x00020000);
+    const __amdgpu_buffer_rsrc_t s_rs = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float*>(scale_t), 0, C * QSCALE_ROWS * 4, 0x00020000);
+    // partial sums: slots of pl.rows (whole row groups) x N, so stores need no row test
+    const __amdgpu_buffer_rsrc_t p_rs = __builtin_amdgcn_make_buffer_rsrc(
+        part, 0, (int)((uint32_t)pl.max_slots * (uint32_t)pl.rows * (uint32_t)N * 4u), 0x00020000);
+    uint32_t a_so = 0, s_so = 0;  // byte offsets of chunk c_a in the activation and scale arrays
+
+    // The int32 accumulators live in the accumulation registers (AGPRs) for the whole
+    // loop.  They are cleared by an MFMA of zeros rather than by moves: the register
+    // allocator keeps a loop-carried tile in AGPRs only if every value that flows into
+    // it comes out of an MFMA; a single VALU-written zero makes it hold the tiles in
+    // VGPRs and copy all of them to and from AGPRs around every unit.
+    const i32x4 zero4 = {0, 0, 0, 0};
+    const i32x16 zero16 = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+    i32x16 iacc[ND][NS][BM];
+#pragma unroll
+    for (int p = 0; p < ND; p++)
+#pragma unroll
+        for (int i = 0; i < NS; i++)
+#pragma unroll
+            for (int bm = 0; bm < BM; bm++)
+                iacc[p][i][bm] = __builtin_amdgcn_mfma_i32_32x32x32_i8(zero4, zero4, zero16, 0, 0, 0);
+
+#pragma unroll
+    for (int j = 0; j < NS * BM * 4; j++) accl[j][tid] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+    u32x4 areg[2][APT];
+    float sreg[2] = {0.f, 0.f};
+    i32x4 aop[AD][BM];  // operand reads run AD - 1 groups ahead of their MFMAs
+
+    int c_a = c_cur, u = u0, u_a = u0;  // chunk of the next activation stage; unit being computed
+    int slot = __builtin_amdgcn_readfirstlane(rec[2]);  // partial slot of this range in tile t_cur
+
+    // end of the scale block that holds chunk c
+    auto block_end = [&](int c) {
+        int e;
+        if (c < c_split) {
+            e = (c / blk0 + 1) * blk0;
+            e = e < c_split ? e : c_split;
+        } else {
+            e = c_split + ((c - c_split) / blk1 + 1) * blk1;
+            e = e < C ? e : C;
+        }
+        return __builtin_amdgcn_readfirstlane(e);
+    };
+    int seg_end = block_end(c_cur);
+
 #define PD_A_NEXT()                                                                      \
     {                                                                                    \
         const int nu_ = u_a + 1 < u1 - 1 ? u_a + 1 : u1 - 1;                             \
@@ -461,15 +471,19 @@ __global__ __launch_bounds__(NT) void qgemm_kernel(const uint4* __restrict__ wp,
             // activations of the first two units straight into stages 0 and 1, those of the
             // third into register stage 1 (step 0 writes them to stage 2), first operand
             // reads of step 0
-            t_w = t_cur; c_w = c_cur; c_a = c_cur;
-            u_w = u; u_a = u;
+            c_a = c_cur;
+            u_a = u;
             a_so = (uint32_t)c_cur * (ND * KC);
             s_so = (uint32_t)c_cur * (QSCALE_ROWS * 4);
-            PD_W_PTRS()
-            PD_FETCH_W(0)
-            PD_FETCH_W(1)
-            if constexpr (R > 2) { PD_FETCH_W(2) }
-            if constexpr (R > 3) { PD_FETCH_W(3) }
+            if (!w_fetched) {  // (the first fill finds its weights already on their way)
+                t_w = t_cur; c_w = c_cur; u_w = u;
+                PD_W_PTRS()
+                PD_FETCH_W(0)
+                PD_FETCH_W(1)
+                if constexpr (R > 2) { PD_FETCH_W(2) }
+                if constexpr (R > 3) { PD_FETCH_W(3) }
+            }
+            w_fetched = false;
             PD_A_NOW(0)
             PD_LOAD_A(1)
             PD_STORE_A(0, 0)
