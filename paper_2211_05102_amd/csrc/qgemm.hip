@@ -390,7 +390,7 @@ __global__ __launch_bounds__(NT) void qgemm_kernel(const uint4* __restrict__ wp,
                         _Pragma("unroll") for (int k = 0; k < 4; k++) {                  \
                             const float f_ = t_[k];                                      \
                             __builtin_amdgcn_raw_buffer_store_b32(                       \
-                                __builtin_bit_cast(uint32_t, f_), p_rs, voff_, so_, 0);  \
+                                __builtin_bit_cast(uint32_t, f_), p_rs, voff_, so_, PD_WRITE_THROUGH);  \
                             so_ += k == 3 ? 5 * rowb_ : rowb_; /* rows 8*q + 4*g + k */  \
                         }                                                                \
                     }                                                                    \
