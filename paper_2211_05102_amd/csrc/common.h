@@ -74,6 +74,12 @@ __host__ __device__ inline size_t skq_table_ints(int T, int G) { return (size_t)
 // and the end-of-kernel write-back of tens of megabytes is then paid as idle time
 // (62B-shaped input projection: 138 -> 124 us).
 #define PD_WRITE_THROUGH 17
+// the same policy for an ordinary store of up to 8 bytes (a relaxed system-scope
+// atomic store is a plain store with sc0 sc1)
+template <typename T>
+__device__ __forceinline__ void store_through(T* p, T v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+}
 
 // round-to-nearest-even fp32 -> bf16 bit pattern (v_cvt_pk_bf16_f32 on gfx950)
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
@@ -153,8 +159,9 @@ __device__ __forceinline__ void quantize_pair_store(float v0, float v1, float in
             d0 = n0;
             d1 = n1;
         }
-        *(reinterpret_cast<uint16_t*>(row_chunk + p * QCHUNK) + lane) =
-            (uint16_t)((d0 & 0xff) | ((d1 & 0xff) << 8));
+        // (written through, see PD_WRITE_THROUGH: the next kernel's projection reads these)
+        store_through(reinterpret_cast<uint16_t*>(row_chunk + p * QCHUNK) + lane,
+                      (uint16_t)((d0 & 0xff) | ((d1 & 0xff) << 8)));
     }
 }
 
