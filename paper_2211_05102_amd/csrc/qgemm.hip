@@ -84,6 +84,7 @@ __global__ __launch_bounds__(NT) void qgemm_kernel(const uint4* __restrict__ wp,
     constexpr int STAGE = ROWS * PITCH + ROWS * 4;  // digits + one scale per row
     static_assert(3 + APT < KB * ND, "stage write fits behind the loads in one unit");
     static_assert(R == 2 || R == 4, "ring depth (even: the activation register stages alternate with the ring slots)");
+    static_assert((KB * ND) % AD == 0, "operand slots rotate evenly across the unit boundary");
     static_assert(3 * STAGE + NS * BM * 16 * NT * 4 <= 160 * 1024, "LDS");
     __shared__ __attribute__((aligned(16))) unsigned char lds[3][STAGE];
     // fp32 sums of the scale blocks of the current tile that this range has finished:
@@ -292,7 +293,7 @@ __global__ __launch_bounds__(NT) void qgemm_kernel(const uint4* __restrict__ wp,
         aop[(gi) % AD][bm], __builtin_bit_cast(i32x4, wreg[s][i][(gi) / ND]),            \
         iacc[(gi) % ND][i][bm], 0, 0, 0);                                                \
     __builtin_amdgcn_sched_barrier(0);
-#define PD_MFMA(buf, s, wbuf, as_load, as_store)                                         \
+#define PD_MFMA(buf, nbuf, s, wbuf, as_load, as_store)                                   \
     {                                                                                    \
         PD_A_NEXT()                                                                      \
         _Pragma("unroll") for (int gi = 0; gi < KB * ND; gi++) {                         \
@@ -300,7 +301,10 @@ __global__ __launch_bounds__(NT) void qgemm_kernel(const uint4* __restrict__ wp,
             /* MFMA executes, so the other work of the group is spread between its    */ \
             /* MFMAs and pinned there.                                                 */ \
             PD_MFMA1(gi, s, 0, 0)                                                        \
+            /* operand reads run AD - 1 groups ahead, across the end of the unit into  */ \
+            /* the stage of the next one (published by the previous barrier)           */ \
             if (gi + AD - 1 < KB * ND) { PD_A_READ(buf, gi + AD - 1, (gi + AD - 1) % AD) } \
+            else { PD_A_READ(nbuf, gi + AD - 1 - KB * ND, (gi + AD - 1) % AD) }           \
             __builtin_amdgcn_sched_barrier(0);                                           \
             if (BM > 1) { PD_MFMA1(gi, s, 0, BM - 1) }                                   \
             /* in the first three groups the loads of the activations three units     */ \
@@ -410,16 +414,14 @@ __global__ __launch_bounds__(NT) void qgemm_kernel(const uint4* __restrict__ wp,
         PD_T(t0_)                                                                        \
         PD_TACC(dbg_top, dbg_last, t0_)                                                  \
         const int nxt_ = o_nxt, wr_ = o_wr;                                              \
-        PD_MFMA(cur, (s) % R, wr_, (s) % 2, ((s) + 1) % 2)                               \
+        PD_MFMA(cur, nxt_, (s) % R, wr_, (s) % 2, ((s) + 1) % 2)                         \
         PD_T(t1_)                                                                        \
         PD_TACC(dbg_mfma, t0_, t1_)                                                      \
-        __builtin_amdgcn_sched_barrier(0);                                               \
-        _Pragma("unroll") for (int g_ = 0; g_ < AD - 1; g_++) { PD_A_READ(nxt_, g_, g_) } \
-        __builtin_amdgcn_sched_barrier(0);                                               \
         PD_T(t2_)                                                                        \
         PD_TACC(dbg_mid, t1_, t2_)                                                       \
-        /* LDS operations of a wave complete in order: all but the (AD-1)*BM reads just */ \
-        /* issued, i.e. this step's stage writes, have landed before the barrier      */  \
+        /* LDS operations of a wave complete in order: all but the (AD-1)*BM reads of   */ \
+        /* the next unit's first groups, i.e. this step's stage writes, have landed     */ \
+        /* before the barrier                                                           */ \
         asm volatile("s_waitcnt lgkmcnt(%0)\n\ts_barrier" ::"n"((AD - 1) * BM) : "memory"); \
         last = cur;                                                                      \
         o_wr = cur;                                                                      \
