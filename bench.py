@@ -65,8 +65,8 @@ def cpu_baseline(w, stack_rows=4, seconds_budget=20.0):
 
 # HBM bytes one launch of the input projection moves, from the rocprofv3 FETCH_SIZE / WRITE_SIZE passes
 # summarised in profiles/hbm_traffic_pmc_c3_62b_layer.txt (counters scaled by a plain 1 GiB copy):
-# (308566.6 * 2.0 + 29696.0 * 1.0) KiB.  Other workloads: not measured.
-TRAFFIC_BYTES_PER_LAUNCH = {"c3_62b": int((308566.6 * 2.0 + 29696.0) * 1024)}
+# (306898.5 * 2.0 + 29696.0 * 1.0) KiB.  Other workloads: not measured.
+TRAFFIC_BYTES_PER_LAUNCH = {"c3_62b": int((306898.5 * 2.0 + 29696.0) * 1024)}
 
 
 def main():
