@@ -94,6 +94,18 @@ struct GemmPlans {
     int slots_in, slots_out;
     int blk_o, blk_a;  // scale blocks (in 128-element chunks) of the attention and SwiGLU outputs
 };
+// Automatic workgroup count of a projection.  More than 64 rows: the projection runs one
+// workgroup grid per 64-row group; all groups together fill the chip once, and the
+// workgroups that stream the same weight range (same x, different row group) are a
+// multiple of 8 apart in launch order, i.e. on the same XCD, where all but the first find
+// the weights in that XCD's L2.
+int auto_workgroups(int B, int K, int N, int c_split, int blk0, int blk1) {
+    const int row_groups = B > 32 ? (B + 63) / 64 : 1;
+    int g_max = PD_GEMM_WORKGROUPS / row_groups;
+    if (row_groups > 1) g_max = g_max / 8 * 8;
+    return pd::qgemm_auto_workgroups(B, K, N, g_max, c_split, blk0, blk1);
+}
+
 GemmPlans gemm_plans(const Shape& s, int B, int g_in_opt, int g_out_opt) {
     GemmPlans p;
     // scale blocks of the projection operands (chunks that share one power-of-two
@@ -103,16 +115,8 @@ GemmPlans gemm_plans(const Shape& s, int B, int g_in_opt, int g_out_opt) {
     const int blk_ln = c_in < 1024 ? c_in : 1024;
     p.blk_o = c_attn < 16 ? c_attn : 16;
     p.blk_a = c_ffn < 16 ? c_ffn : 16;
-    // More than 64 rows: the projection runs one workgroup grid per 64-row group.  All
-    // groups together fill the chip once, and the workgroups that stream the same weight
-    // range (same x, different row group) are a multiple of 8 apart in launch order, i.e.
-    // on the same XCD, where all but the first find the weights in that XCD's L2.
-    const int row_groups = B > 32 ? (B + 63) / 64 : 1;
-    int g_auto = PD_GEMM_WORKGROUPS / row_groups;
-    if (row_groups > 1) g_auto = g_auto / 8 * 8;
-    const int g_in = g_in_opt > 0 ? g_in_opt : pd::qgemm_auto_workgroups(B, s.d, s.n_in, g_auto, 0, 1, blk_ln);
-    const int g_out = g_out_opt > 0 ? g_out_opt
-                                    : pd::qgemm_auto_workgroups(B, s.k_out, s.d, g_auto, c_attn, p.blk_o, p.blk_a);
+    const int g_in = g_in_opt > 0 ? g_in_opt : auto_workgroups(B, s.d, s.n_in, 0, 1, blk_ln);
+    const int g_out = g_out_opt > 0 ? g_out_opt : auto_workgroups(B, s.k_out, s.d, c_attn, p.blk_o, p.blk_a);
     p.in = pd::qgemm_plan(B, s.d, s.n_in, g_in, 0, 1, blk_ln, &p.slots_in);
     p.out = pd::qgemm_plan(B, s.k_out, s.d, g_out, c_attn, p.blk_o, p.blk_a, &p.slots_out);
     return p;
@@ -519,7 +523,7 @@ struct QgemmWs {
 QgemmWs qgemm_ws(int B, int K, int N, int workgroups) {
     QgemmWs q;
     int slots = 1;
-    q.pl = pd::qgemm_plan(B, K, N, workgroups > 0 ? workgroups : PD_GEMM_WORKGROUPS, 0, 1, 1, &slots);
+    q.pl = pd::qgemm_plan(B, K, N, workgroups > 0 ? workgroups : auto_workgroups(B, K, N, 0, 1, 1), 0, 1, 1, &slots);
     size_t o = 0;
     q.part = o; o += align256((size_t)slots * q.pl.rows * N * 4);
     q.qa = o; o += align256((size_t)B * K * 3);
@@ -547,7 +551,8 @@ pd_status pd_qgemm_plan(int32_t B, int32_t K, int32_t N, int32_t workgroups, int
     if (c_split < 0 || c_split > K / 128 || blk0 < 1 || blk0 > 1024 || blk1 < 1 || blk1 > 1024)
         return fail(PD_ERR_RANGE, "scale blocks out of range");
     int slots = 1;
-    const pd::SkqPlan pl = pd::qgemm_plan(B, K, N, workgroups > 0 ? workgroups : PD_GEMM_WORKGROUPS, c_split, blk0, blk1, &slots);
+    const pd::SkqPlan pl = pd::qgemm_plan(B, K, N, workgroups > 0 ? workgroups : auto_workgroups(B, K, N, c_split, blk0, blk1),
+                                          c_split, blk0, blk1, &slots);
     counts[0] = pl.G; counts[1] = pl.T; counts[2] = pl.C; counts[3] = pl.rows; counts[4] = slots;
     const long long U = (long long)pl.T * pl.C;
     for (int g = 0; g <= pl.G; g++) {

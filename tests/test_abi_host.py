@@ -113,6 +113,8 @@ def test_projection_work_split_covers_every_unit_once(binding, B, K, N, wg, c_sp
     G, T, C = counts["workgroups"], counts["tiles"], counts["chunks_per_tile"]
     U = T * C
     assert C == K // 128 and T == -(-N // 256) and 1 <= G <= max(1, min(wg or 256, U))
+    if wg == 0 and B <= 64 and U >= 4096:
+        assert G >= 224  # the automatic count gives up at most one eighth of the compute units
     assert counts["rows"] % 32 == 0 and counts["rows"] >= B and counts["rows"] - B < 64
     # ranges: contiguous, ordered, cover [0, U) exactly once, balanced to within the alignment
     assert begin[0] == 0 and begin[G] == U and all(begin[g] <= begin[g + 1] for g in range(G))
@@ -140,3 +142,14 @@ def test_projection_work_split_rejects_bad_arguments(binding):
     assert L.pd_qgemm_plan(i32(8), i32(128), i32(32), i32(5000), i32(0), i32(1), i32(1), counts, None, None, None) == binding.PD_ERR_RANGE
     assert L.pd_qgemm_plan(i32(8), i32(128), i32(32), i32(0), i32(2), i32(1), i32(1), counts, None, None, None) == binding.PD_ERR_RANGE
     assert L.pd_qgemm_plan(i32(8), i32(128), i32(32), i32(0), i32(0), i32(1), i32(1), None, None, None, None) == binding.PD_ERR_NULL
+
+
+def test_automatic_split_of_the_62b_projections_is_even(binding):
+    # the kernel is bandwidth-bound: its time follows the longest range, so the automatic
+    # workgroup count prefers an even split to using every compute unit
+    counts, begin, _, _ = binding.qgemm_plan(64, 8192, 74240, 0, 0, 1, 64)
+    sizes = {begin[g + 1] - begin[g] for g in range(counts["workgroups"])}
+    assert counts["workgroups"] == 232 and sizes == {80}
+    counts, begin, _, _ = binding.qgemm_plan(64, 40960, 8192, 0, 64, 16, 16)
+    sizes = {begin[g + 1] - begin[g] for g in range(counts["workgroups"])}
+    assert counts["workgroups"] == 256 and sizes == {40}
