@@ -69,6 +69,35 @@ def cpu_baseline(w, stack_rows=4, seconds_budget=20.0):
 TRAFFIC_BYTES_PER_LAUNCH = {"c3_62b": int((306898.5 * 2.0 + 29696.0) * 1024)}
 
 
+def time_workload(w, steps, warmup):
+    """Graph-replay time of one decode step of workload `w` (all inputs resident)."""
+    import torch
+    from workloads import configs as C
+    from paper_2211_05102_amd import harness
+    st = harness.DeviceStack(w)
+    positions = st.positions.cpu().tolist()
+    bytes_step = C.algorithmic_bytes(w, positions)
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        st.dec.graph_capture(st.packed, st.k_cache, st.v_cache, st.x_in, st.positions, w.l_ctx,
+                             st.x_out, st.workspace, stream)
+        for _ in range(warmup):
+            st.dec.graph_replay(stream)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            st.dec.graph_replay(stream)
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / steps
+        st.dec.check_async(st.workspace, stream)
+    st.dec.graph_release()
+    del st
+    torch.cuda.empty_cache()
+    gbps = bytes_step / dt / 1e9
+    return {"ms_per_step": dt * 1e3, "GB/s": gbps, "hbm_peak_frac": gbps / HBM_PEAK_GBPS,
+            "tokens_per_s": w.batch / dt}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -83,6 +112,9 @@ def main():
     ap.add_argument("--gemm-wg-out", type=int, default=0)
     ap.add_argument("--attn-bps", type=int, default=0)
     ap.add_argument("--act-digits", type=int, default=0)
+    ap.add_argument("--all-configs", action="store_true",
+                    help="also time the other named workloads (graph replay, 5 steps each) and add them to the "
+                         "JSON line as per_config; the headline value stays the --workload one")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three plain 1 GiB device copies (reference for scaling rocprofv3's "
                          "FETCH_SIZE / WRITE_SIZE counters in the --pmc passes)")
@@ -192,9 +224,15 @@ def main():
                      "bytes_per_launch": k_bytes, "avg_launch_us": k_avg_s * 1e6},
         "kernels": per_kernel,
     }
+    del st
+    torch.cuda.empty_cache()
+    if args.all_configs:
+        out["per_config"] = {w.name: {"ms_per_step": ms_per_step, "GB/s": gbps, "hbm_peak_frac": gbps / HBM_PEAK_GBPS}}
+        for name in ("c1_tiny", "c2_8b", "c4_540b_shard8", "c5_62b_long"):
+            if name == args.workload:
+                continue
+            out["per_config"][name] = time_workload(WORKLOADS[name], steps=5, warmup=2)
     if not args.no_cpu_baseline:
-        del st
-        torch.cuda.empty_cache()
         out["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(out))
 
