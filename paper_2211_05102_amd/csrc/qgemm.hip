@@ -68,7 +68,7 @@ __device__ long long pd_dbg[4096 * 8];
 // vmcnt bookkeeping keeps the ring in flight.  Every step issues the same loads
 // unconditionally (past the end of the range the last unit is fetched again,
 // an L2 hit) so that no control-flow join weakens those waits.
-template <int BM, int NS, int ND, int R, int AD>
+template <int BM, int NS, int ND, int R, int AD, int WAUX>
 __global__ __launch_bounds__(NT) void qgemm_kernel(const uint4* __restrict__ wp,
                                                       const unsigned char* __restrict__ qa,
                                                       const float* __restrict__ scale_t,
@@ -136,10 +136,11 @@ __global__ __launch_bounds__(NT) void qgemm_kernel(const uint4* __restrict__ wp,
         st_ = st_ < n_sub ? st_ : n_sub - 1; /* ragged last tile: result dropped */      \
         w_so[i] = (uint32_t)st_ * (uint32_t)(K * 32) + (uint32_t)c_w * (KC * 32);        \
     }
-    // non-temporal: each weight byte is read once per step
+    // WAUX = 2 (non-temporal): each weight byte is read once per step; 0 when several row
+    // groups stream the same weights and the later ones are meant to find them in L2
 #define PD_W_LOAD(s, kb)                                                                 \
     _Pragma("unroll") for (int i = 0; i < NS; i++)                                       \
-        wreg[s][i][kb] = __builtin_amdgcn_raw_buffer_load_b128(w_rs, lane16 + (kb) * 1024, w_so[i], 2);
+        wreg[s][i][kb] = __builtin_amdgcn_raw_buffer_load_b128(w_rs, lane16 + (kb) * 1024, w_so[i], WAUX);
 #define PD_W_REFILL(s, kb) PD_W_LOAD(s, kb)
     // (past the end of the range the last unit is fetched again: an L2 hit; selects
     // rather than branches, except for the rare move to the next tile)
@@ -733,12 +734,12 @@ hipError_t launch_qgemm(const void* wp, const void* qa, const float* scale_t, fl
     dim3 grid(pl.G, (B + 32 * bm - 1) / (32 * bm)), block(NT);
     const uint4* w4 = reinterpret_cast<const uint4*>(wp);
     const unsigned char* q = reinterpret_cast<const unsigned char*>(qa);
-#define PD_LAUNCH(BMv, NSv, RING, ADv)                                                           \
+#define PD_LAUNCH(BMv, NSv, RING, ADv, WAUXv)                                                    \
     do {                                                                                    \
         if (nd == 3)                                                                        \
-            qgemm_kernel<BMv, NSv, 3, RING, ADv><<<grid, block, 0, stream>>>(w4, q, scale_t, part, B, K, N, pl); \
+            qgemm_kernel<BMv, NSv, 3, RING, ADv, WAUXv><<<grid, block, 0, stream>>>(w4, q, scale_t, part, B, K, N, pl); \
         else                                                                                \
-            qgemm_kernel<BMv, NSv, 2, RING, ADv><<<grid, block, 0, stream>>>(w4, q, scale_t, part, B, K, N, pl); \
+            qgemm_kernel<BMv, NSv, 2, RING, ADv, WAUXv><<<grid, block, 0, stream>>>(w4, q, scale_t, part, B, K, N, pl); \
     } while (0)
     if (nd != 2 && nd != 3) return hipErrorInvalidValue;
     if (pl.blk0 < 1 || pl.blk0 > 1024 || pl.blk1 < 1 || pl.blk1 > 1024 || pl.c_split < 0 || pl.c_split > K / 128)
@@ -747,8 +748,9 @@ hipError_t launch_qgemm(const void* wp, const void* qa, const float* scale_t, fl
     if ((long long)B * K * nd >= (1ll << 31) || (long long)K * N >= (1ll << 32)) return hipErrorInvalidValue;
     if ((long long)pl.T * pl.C >= (1ll << 31)) return hipErrorInvalidValue;
     if ((long long)pl.max_slots * pl.rows * N * 4 >= (1ll << 32)) return hipErrorInvalidValue;
-    if (bm == 1) PD_LAUNCH(1, 2, 4, 4);  // rings as in qgemm_ring()
-    else PD_LAUNCH(2, 2, 2, 4);
+    if (bm == 1) PD_LAUNCH(1, 2, 4, 4, 2);  // rings as in qgemm_ring()
+    else if (grid.y > 1) PD_LAUNCH(2, 2, 2, 4, 0);
+    else PD_LAUNCH(2, 2, 2, 4, 2);
 #undef PD_LAUNCH
     return hipGetLastError();
 }
