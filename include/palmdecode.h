@@ -67,8 +67,10 @@ enum {
 };
 
 /* Model description (Section 2.2 notation: d_model = E, d_ff = F, n_heads = H).
- * Supported: d_model % 128 == 0, (H*d_head + d_ff) % 128 == 0, d_ff % 32 == 0,
- * d_head in {64, 128, 256}, 1 <= n_heads <= 32, n_kv_heads == 1. */
+ * Supported: d_model % 128 == 0, d_ff % 128 == 0, (H*d_head) % 128 == 0,
+ * d_head in {64, 128, 256}, 1 <= n_heads <= 32, n_kv_heads == 1; each projection
+ * matrix smaller than 4 GiB; batch 1..256; L_ctx a multiple of 32.  Anything else
+ * is refused with PD_ERR_SHAPE by every call that takes the description. */
 typedef struct pd_model_desc {
     int32_t n_layers;
     int32_t d_model;
@@ -86,7 +88,9 @@ typedef struct pd_handle pd_handle;
 const char* pd_status_string(pd_status code);
 const char* pd_last_error(void);
 
-/* ---- sizes: pure host functions ------------------------------------------ */
+/* ---- sizes: pure host functions ------------------------------------------
+ * Section 2 ("Memory costs") counts exactly these two tensors per step: the
+ * weights and the KV cache; the third size is this library's own scratch. */
 
 /* Bytes of one packed layer (int8 matrices, fp32 scales and gain, 256-aligned).
  * The packed stack is n_layers such blobs back to back. */
@@ -98,11 +102,12 @@ pd_status pd_workspace_bytes(const pd_model_desc* desc, int32_t B, int32_t L_ctx
 
 /* ---- handle --------------------------------------------------------------- */
 
-/* Validates and copies `desc`.  The handle owns host state only (launch plan,
- * an optional captured graph). */
+/* Validates and copies `desc` (the model of Section 2.2 / Section 3.4).  The
+ * handle owns host state only (launch plan, an optional captured graph). */
 pd_status pd_create(const pd_model_desc* desc, pd_handle** out);
 pd_status pd_destroy(pd_handle* h);
-/* Tuning knobs: "gemm_workgroups_in", "gemm_workgroups_out" (workgroups that
+/* Tuning knobs (not part of the decode contract; defaults are what the
+ * benchmark times): "gemm_workgroups_in", "gemm_workgroups_out" (workgroups that
  * share the weight matrix of the input / output projection, 0 = automatic:
  * at most one per compute unit and 64-row group, chosen so that the ranges come
  * out even; values above 256 are rejected),
@@ -112,7 +117,8 @@ pd_status pd_destroy(pd_handle* h);
  * return PD_ERR_RANGE. */
 pd_status pd_set_option(pd_handle* h, const char* name, int32_t value);
 
-/* Event timing of one kernel class, for the roofline report.  Option
+/* Event timing of one kernel class, for the roofline report (measurement
+ * interface; no passage of the paper defines it).  Option
  * "profile_kernel" = 1 (input projection), 2 (attention + combine), 3 (output
  * projection), 4 (input epilogue), 5 (output epilogue), 0 = off: while on, every
  * launch of that class made by pd_decode_step/pd_decode_layer is bracketed by
@@ -135,7 +141,10 @@ pd_status pd_pack_layer(pd_handle* h, const int8_t* w_in, const uint16_t* s_in,
 pd_status pd_pack_matrix(const int8_t* w, int32_t K, int32_t N, void* packed_w, void* stream);
 
 /* One layer of the cache, canonical [B][L_ctx][dh] <-> library layout, at layer
- * index `layer` of the library-side K or V cache (`is_v` selects the V layout). */
+ * index `layer` of the library-side K or V cache (`is_v` selects the V layout).
+ * The cache is the per-sequence K/V store of Section 2 ("Memory costs"), with one
+ * K/V head per layer (Section 3.3); the library layout is a permutation of it
+ * inside 32-token blocks, so slot (l, b, t) of one is slot (l, b, t) of the other. */
 pd_status pd_kv_import(pd_handle* h, const uint16_t* canonical, void* cache, int32_t layer,
                        int32_t B, int32_t L_ctx, int32_t is_v, void* stream);
 pd_status pd_kv_export(pd_handle* h, const void* cache, uint16_t* canonical, int32_t layer,
@@ -177,7 +186,9 @@ pd_status pd_decode_layer(pd_handle* h, int32_t layer, const void* packed_layer,
                           size_t workspace_bytes, void* stream);
 
 /* Synchronises `stream`, then reports the per-row position flags the most
- * recent step on this `workspace` left: PD_OK or PD_ERR_POSITION. */
+ * recent step on this `workspace` left: PD_OK or PD_ERR_POSITION.
+ * (Section 2.2: a step decodes the token at positions[b]; a position outside
+ * the cache has no defined result.) */
 pd_status pd_check_async(pd_handle* h, void* workspace, void* stream);
 
 /* ---- single steps of the path (tests, profiling) -------------------------- */
@@ -217,7 +228,9 @@ pd_status pd_mqa_attend(pd_handle* h, int32_t layer, const float* q, const void*
                         const void* v_cache, const int32_t* positions, int32_t B, int32_t L_ctx,
                         float* o, void* workspace, size_t workspace_bytes, void* stream);
 
-/* ---- graph replay --------------------------------------------------------- */
+/* ---- graph replay ---------------------------------------------------------
+ * Section 2.2: generation repeats the same step once per token; replaying a
+ * captured step removes the per-kernel launch cost from that loop. */
 
 /* Captures pd_decode_step(...) with these arguments into a HIP graph owned by
  * the handle; pd_graph_replay() launches it.  Valid while every pointer, B and

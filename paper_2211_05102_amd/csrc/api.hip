@@ -42,6 +42,9 @@ pd_status check_desc(const pd_model_desc* m, Shape* s) {
     if ((m->n_heads * m->d_head) % 128) return fail(PD_ERR_SHAPE, "n_heads*d_head must be a multiple of 128");
     long long n_in = (long long)m->n_heads * m->d_head + 2LL * m->d_head + 2LL * m->d_ff;
     if (n_in > (1 << 24) || k_out > (1 << 24) || m->d_model > (1 << 20)) return fail(PD_ERR_SHAPE, "model too large");
+    // the kernels address each matrix through a 32-bit buffer descriptor
+    if ((long long)m->d_model * n_in >= (1ll << 32) || k_out * m->d_model >= (1ll << 32))
+        return fail(PD_ERR_SHAPE, "a projection matrix must be smaller than 4 GiB");
     if (!(m->rope_base > 1.0f) || !(m->ln_eps > 0.0f)) return fail(PD_ERR_SHAPE, "rope_base must exceed 1 and ln_eps must be positive");
     if (s) {
         s->L = m->n_layers; s->d = m->d_model; s->H = m->n_heads; s->dh = m->d_head; s->F = m->d_ff;
@@ -122,13 +125,16 @@ GemmPlans gemm_plans(const Shape& s, int B, int g_in_opt, int g_out_opt) {
     return p;
 }
 
-// Upper bound of the segments in one tile for ANY workgroup count up to the automatic
-// one: scale-block starts inside a tile, plus the workgroup range starts that can
-// fall into one tile, plus one.
-int slots_bound(pd::SkqPlan pl) {
-    pl.G = 1;
-    const int block_starts = pd::skq_segments_upto(0, pl.C - 1, pl);
-    return 1 + block_starts + PD_GEMM_WORKGROUPS / pl.T + 1;
+// Upper bound of the partial-sum slots of one tile for ANY workgroup count up to
+// PD_GEMM_WORKGROUPS: one, plus the workgroup ranges that can start strictly inside a
+// tile of C chunks.  Range starts are floor(g*U/G) rounded down to the ring (at most 4
+// units), so two consecutive starts are at least floor(U/G) - 3 units apart, and more
+// workgroups only make the ranges shorter.
+int slots_bound(const pd::SkqPlan& pl) {
+    const long long U = (long long)pl.T * pl.C;
+    long long min_len = U / PD_GEMM_WORKGROUPS - 3;
+    if (min_len < 1) min_len = 1;
+    return 1 + (int)((pl.C - 1 + min_len - 1) / min_len);
 }
 
 // workspace carving; the partial-sum areas hold slots_bound() slots, so a workgroup
@@ -161,6 +167,18 @@ Workspace workspace_layout(const Shape& s, int B, int L_ctx) {
 }
 
 size_t kv_layer_elems(const Shape& s, int B, int L_ctx) { return (size_t)B * L_ctx * s.dh; }
+
+// Limits that depend on the batch: the projection operand and the partial-sum slots
+// are also addressed through 32-bit buffer descriptors.
+pd_status check_limits(const Shape& s, int B) {
+    const long long K_max = s.k_out > s.d ? s.k_out : s.d;
+    if ((long long)B * K_max * 3 >= (1ll << 31)) return fail(PD_ERR_SHAPE, "batch x projection depth too large");
+    const GemmPlans gp = gemm_plans(s, B, 0, 0);
+    if ((long long)slots_bound(gp.in) * gp.in.rows * s.n_in * 4 >= (1ll << 32) ||
+        (long long)slots_bound(gp.out) * gp.out.rows * s.d * 4 >= (1ll << 32))
+        return fail(PD_ERR_SHAPE, "batch x projection width too large");
+    return PD_OK;
+}
 
 }  // namespace
 
@@ -294,6 +312,7 @@ pd_status check_step_args(pd_handle* h, const void* packed, void* kc, void* vc, 
     if (!packed || !kc || !vc || !x_in || !positions || !out || !ws) return fail(PD_ERR_NULL, "NULL device pointer");
     pd_status rc = check_batch(B, L_ctx);
     if (rc != PD_OK) return rc;
+    if ((rc = check_limits(h->s, B)) != PD_OK) return rc;
     if (!aligned(packed, 256) || !aligned(kc, 256) || !aligned(vc, 256) || !aligned(ws, 256))
         return fail(PD_ERR_ALIGN, "packed weights, caches and workspace must be 256-byte aligned");
     if (!aligned(x_in, 16) || !aligned(out, 16) || !aligned(positions, 4))
@@ -347,6 +366,7 @@ pd_status pd_workspace_bytes(const pd_model_desc* desc, int32_t B, int32_t L_ctx
     pd_status rc = check_desc(desc, &s);
     if (rc != PD_OK) return rc;
     if ((rc = check_batch(B, L_ctx)) != PD_OK) return rc;
+    if ((rc = check_limits(s, B)) != PD_OK) return rc;
     if (!bytes) return fail(PD_ERR_NULL, "bytes is NULL");
     *bytes = workspace_layout(s, B, L_ctx).total;
     return PD_OK;

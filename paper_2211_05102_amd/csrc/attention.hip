@@ -33,13 +33,6 @@
 
 namespace pd {
 
-#ifdef PD_DBG_TIMING
-__device__ long long pd_dbg_att[4096 * 8];
-#define PD_AT(x) const long long x = clock64();
-#else
-#define PD_AT(x)
-#endif
-
 // o[b][h*dh + c] = sum_s w_s O_s[c] / sum_s w_s l_s,  w_s = 2^(m_s - max m), splits in index order.
 // One workgroup per scale block of the row (blk_o chunks of 128 elements, at most
 // 16); each wave takes every fourth chunk, two adjacent channels per lane.  The
@@ -183,7 +176,6 @@ __global__ __launch_bounds__(256) void mqa_attend_kernel(
     constexpr int SMEM_U4 = 2 * KJ * 64 > DB * 3 * 4 * 64 ? 2 * KJ * 64 : DB * 3 * 4 * 64;
     __shared__ uint4 smem[SMEM_U4];
 
-    PD_AT(ta0)
     const int b = blockIdx.y, split = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63;
     // (uniform by construction; saying so keeps the buffer offsets derived from it scalar --
@@ -258,7 +250,6 @@ __global__ __launch_bounds__(256) void mqa_attend_kernel(
         }
     }
     __syncthreads();
-    PD_AT(ta1)
 
     for (int blk = first; blk < blk1; blk += 4) {
         const int blk_off = blk * BLK_U4 * 16, next_off = (blk + 4) * BLK_U4 * 16;
@@ -347,9 +338,7 @@ __global__ __launch_bounds__(256) void mqa_attend_kernel(
                     __builtin_amdgcn_raw_buffer_load_b128(k_rs, lane16, next_off + (db * 2 + kk) * 1024, 2);
             }
     }
-    PD_AT(ta2)
     __syncthreads();  // every wave is done with the q operands: smem becomes the merge buffer
-    PD_AT(ta3)
 
     // ---- merge the 4 waves (a wave without blocks has m = -inf, l = 0, O = 0).  Output
     // block db belongs to wave db % 4: every wave leaves its scaled sums of the blocks it
@@ -405,22 +394,7 @@ __global__ __launch_bounds__(256) void mqa_attend_kernel(
             if (l32 < H) *reinterpret_cast<f32x4*>(orow + db * 32 + 8 * i + 4 * g) = sum;
         }
     }
-#ifdef PD_DBG_TIMING
-    PD_AT(ta4)
-    if (lane == 0) {
-        long long* d_ = pd_dbg_att + ((blockIdx.y * gridDim.x + blockIdx.x) * 4 + wave) * 8;
-        if ((blockIdx.y * gridDim.x + blockIdx.x) * 4 + wave < 4096) {
-            d_[0] = ta1 - ta0; d_[1] = ta2 - ta1; d_[2] = ta3 - ta2; d_[3] = ta4 - ta3; d_[4] = wall_clock64();
-        }
-    }
-#endif
 }
-
-#ifdef PD_DBG_TIMING
-extern "C" int pd_dbg_read_att(long long* host, int n) {
-    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(pd_dbg_att), sizeof(long long) * n);
-}
-#endif
 
 // canonical [B][L_ctx][dh]  <->  library block layout, one element per thread
 __global__ __launch_bounds__(256) void kv_convert_kernel(const uint16_t* __restrict__ src,

@@ -47,15 +47,6 @@ __device__ __forceinline__ void lds_barrier() {
 
 constexpr int NT = 256;  // threads per GEMM workgroup: 4 waves, one per SIMD, 512 registers each
 
-#ifdef PD_DBG_TIMING /* tuning experiment: per-phase cycle counts of wave 0 of each workgroup */
-__device__ long long pd_dbg[4096 * 8];
-#define PD_T(x) const long long x = clock64();
-#define PD_TACC(a, x, y) a += (y) - (x);
-#else
-#define PD_T(x)
-#define PD_TACC(a, x, y)
-#endif
-
 // BM: 32-row batch blocks held in accumulators; NS: 32-column subtiles per wave;
 // ND: digit planes; R: weight units per wave held in a register ring; AD: operand
 // reads run AD - 1 MFMA groups ahead.  grid = (G workgroups, row groups of 32*BM
@@ -92,9 +83,6 @@ __global__ __launch_bounds__(NT) void qgemm_kernel(const uint4* __restrict__ wp,
     // unit loop leaves no registers for them
     __shared__ f32x4 accl[NS * BM * 4][NT];
 
-#ifdef PD_DBG_TIMING
-    const long long dbg_k0 = clock64();
-#endif
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform: lets addresses stay scalar
     const int g = lane >> 5, l32 = lane & 31;
@@ -412,14 +400,8 @@ __global__ __launch_bounds__(NT) void qgemm_kernel(const uint4* __restrict__ wp,
     // the first operand reads of the next step are already in flight across it.
 #define PD_STEP(s)                                                                       \
     {                                                                                    \
-        PD_T(t0_)                                                                        \
-        PD_TACC(dbg_top, dbg_last, t0_)                                                  \
         const int nxt_ = o_nxt, wr_ = o_wr;                                              \
         PD_MFMA(cur, nxt_, (s) % R, wr_, (s) % 2, ((s) + 1) % 2)                         \
-        PD_T(t1_)                                                                        \
-        PD_TACC(dbg_mfma, t0_, t1_)                                                      \
-        PD_T(t2_)                                                                        \
-        PD_TACC(dbg_mid, t1_, t2_)                                                       \
         /* LDS operations of a wave complete in order: all but the (AD-1)*BM reads of   */ \
         /* the next unit's first groups, i.e. this step's stage writes, have landed     */ \
         /* before the barrier                                                           */ \
@@ -428,15 +410,7 @@ __global__ __launch_bounds__(NT) void qgemm_kernel(const uint4* __restrict__ wp,
         o_wr = cur;                                                                      \
         cur = nxt_;                                                                      \
         o_nxt = wr_;                                                                     \
-        PD_T(t3_)                                                                        \
-        PD_TACC(dbg_bar, t2_, t3_)                                                       \
-        PD_TACC(dbg_last, dbg_last, t3_)                                                 \
     }
-#ifdef PD_DBG_TIMING
-    long long dbg_top = 0, dbg_mfma = 0, dbg_mid = 0, dbg_bar = 0, dbg_x1 = 0, dbg_x2 = 0, dbg_last = clock64();
-    const long long dbg_t0 = dbg_last, dbg_w0 = wall_clock64();
-    long long dbg_first = 0;
-#endif
     // A segment = the run of units of one scale block inside this range: clear the
     // int32 accumulators, run its units, fold the int32 sums into the fp32 sums of the
     // tile.  (A fold inside the unit loop would put VALU reads and writes of the
@@ -544,13 +518,6 @@ __global__ __launch_bounds__(NT) void qgemm_kernel(const uint4* __restrict__ wp,
         }
     }
 #undef PD_END_SEGMENT
-#ifdef PD_DBG_TIMING
-    if (tid == 0 && blockIdx.y == 0 && blockIdx.x < 2048) {
-        long long* d_ = pd_dbg + (c_split ? 2048 * 8 : 0) + blockIdx.x * 8;
-        d_[0] = clock64() - dbg_t0; d_[1] = wall_clock64() - dbg_w0; d_[2] = dbg_top; d_[3] = dbg_mfma;
-        d_[4] = dbg_x1; d_[5] = dbg_x2; d_[6] = u1 - u0; d_[7] = dbg_first;
-    }
-#endif
 #undef PD_FETCH_W
 #undef PD_A_NEXT
 #undef PD_A_NOW
@@ -755,11 +722,6 @@ hipError_t launch_qgemm(const void* wp, const void* qa, const float* scale_t, fl
     return hipGetLastError();
 }
 
-#ifdef PD_DBG_TIMING
-extern "C" int pd_dbg_read(long long* host, int n) {
-    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(pd_dbg), sizeof(long long) * n);
-}
-#endif
 
 hipError_t launch_quantize_bf16(const uint16_t* a, void* qa, float* scale_t, int B, int K, int nd,
                                 hipStream_t stream) {

@@ -175,8 +175,32 @@ def test_attention_vs_oracle(pd, H, dh, L, pos):
 
 # ------------------------------------------------------- one layer / stack ---
 
+def check_every_cache_slot(w, st, pos_t, poison):
+    """On the device, for EVERY layer and EVERY sequence: the cache after the step
+    equals the seeded cache it was built from bit for bit in every slot except
+    (l, b, P_b), and that slot did change.  The original cache is drawn again from
+    its seed layer by layer, so no second copy of a 137 GB cache is needed."""
+    B, L = st.B, w.l_ctx
+    t = torch.arange(L, device="cuda")[None, :]
+    p = pos_t.to("cuda").long()[:, None]
+    live, at_p = t <= p, t == p
+    for l in range(w.n_layers):
+        k0, v0 = synth.kv_layer(w, l, "cuda", batch=B)
+        if poison:
+            k0 = torch.where(live[:, :, None], k0, torch.full_like(k0, float("nan")))
+            v0 = torch.where(live[:, :, None], v0, torch.full_like(v0, float("inf")))
+        kg, vg = st.export_kv(l)
+        for name, got, ref in (("K", kg, k0), ("V", vg, v0)):
+            changed = (got.view(torch.int16) != ref.view(torch.int16)).any(dim=2)  # [B, L]
+            if not torch.equal(changed, at_p):
+                bad = torch.nonzero(changed != at_p)[:8].tolist()
+                raise AssertionError(f"{name} cache, layer {l}: slots that changed are not exactly "
+                                     f"(b, P_b); first offenders (b, t): {bad}")
+        del k0, v0, kg, vg
+
+
 def check_cache_append(w, st, kcs_after, vcs_after, kcs_before, vcs_before, rows, positions):
-    """Exactly slot P_b of each checked row changed (bit-exact indexing); the
+    """Followed rows: exactly slot P_b changed (bit-exact indexing) and the
     appended values agree with the oracle's to a bf16 step."""
     for l in range(w.n_layers):
         kg, vg = st.export_kv(l)
@@ -221,7 +245,29 @@ def run_stack_parity(pd, w, rows=None, poison=True, name=None, positions=None):
     assert np.all(np.isfinite(gpu))
     scaled, rel = report(name or w.name, gpu, widen(oracle.f64_to_bf16_bits(x64)), x64)
     check_cache_append(w, st, kcs, vcs, kcs0, vcs0, rows, pos)
+    check_every_cache_slot(w, st, pos_t, poison)
     return st, scaled, rel, gpu, x64
+
+
+def assert_bitwise_repeatable(st, first):
+    """Fixed split counts and summation orders, no float atomics: the same step
+    (it re-appends the same slot) gives the same bits every time."""
+    first = first.clone()
+    for _ in range(2):
+        again = st.step()
+        torch.cuda.synchronize()
+        assert torch.equal(first.view(torch.int16), again.view(torch.int16))
+
+
+@pytest.fixture
+def big_memory():
+    """The large stacks need most of the HBM: return what earlier tests left cached."""
+    import gc
+    gc.collect()
+    torch.cuda.empty_cache()
+    yield
+    gc.collect()
+    torch.cuda.empty_cache()
 
 
 def test_decode_step_tiny_workload_raw_tolerance(pd):
@@ -293,41 +339,79 @@ def test_decode_layer_partial_without_residual(pd):
         assert scaled <= MAX_SCALED and rel <= REL_L2
 
 
-def test_decode_step_8b_shaped_full_batch(pd):
+def test_decode_step_8b_shaped_full_batch(pd, big_memory):
     w = WORKLOADS["c2_8b"]
     st, scaled, rel, _, _ = run_stack_parity(pd, w)
     assert scaled <= MAX_SCALED and rel <= REL_L2, (scaled, rel)
-    # run-to-run bitwise reproducibility (fixed split counts, no float atomics);
-    # the step re-appends the same slot, so it can simply be repeated
-    a = st.step().clone()
-    b = st.step().clone()
-    torch.cuda.synchronize()
-    assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+    assert_bitwise_repeatable(st, st.x_out)
 
 
-def test_decode_step_62b_shaped_sampled_rows(pd):
+def test_decode_step_62b_shaped_sampled_rows(pd, big_memory):
     # full 64-layer stack in the launch configuration the benchmark times; the
-    # oracle follows 6 of the 64 sequences through all layers (rows are independent)
+    # oracle follows 6 of the 64 sequences through all layers (rows are independent),
+    # the append check covers all 64
     w = WORKLOADS["c3_62b"]
     st, scaled, rel, _, _ = run_stack_parity(pd, w, rows=[0, 63, 17, 42, 5, 30])
     assert scaled <= MAX_SCALED and rel <= REL_L2, (scaled, rel)
+    assert_bitwise_repeatable(st, st.x_out)
 
 
-def test_decode_step_540b_shard_shaped_layers(pd):
-    # layer shape of one eighth of the 540B model under 1D weight-stationary partitioning
-    # (Section 3.2.1: 6 of 48 heads, 9216 of 73728 FFN columns, full d_model 18432),
-    # batch 32, KV length 2048; 2 of the 118 layers, the shard's contribution chained locally
-    w = WORKLOADS["c4_540b_shard8"].with_(n_layers=2, name="c4_540b_shard8[2 layers]")
+def test_decode_step_540b_shard_full_depth(pd, big_memory):
+    # one eighth of the 540B model under 1D weight-stationary partitioning (Section 3.2.1:
+    # 6 of 48 heads, 9216 of 73728 FFN columns, full d_model 18432), batch 32, KV length
+    # 2048, all 118 layers, the shard's contribution chained locally; the oracle follows
+    # the first, the last and one other sequence
+    w = WORKLOADS["c4_540b_shard8"]
     st, scaled, rel, _, _ = run_stack_parity(pd, w, rows=[0, 31, 13])
     assert scaled <= MAX_SCALED and rel <= REL_L2, (scaled, rel)
+    assert_bitwise_repeatable(st, st.x_out)
 
 
-def test_decode_step_62b_long_context_shaped_layer(pd):
+def test_decode_step_62b_long_context_full_depth(pd, big_memory):
     # batch 256 (four 64-row groups in the projections), KV capacity 8192 with ragged
-    # lengths in [4096, 8192) (many KV splits per row, ragged last blocks); 1 of the 64 layers
-    w = WORKLOADS["c5_62b_long"].with_(n_layers=1, name="c5_62b_long[1 layer]")
-    st, scaled, rel, _, _ = run_stack_parity(pd, w, rows=[0, 255, 64, 129, 7])
+    # lengths in [4096, 8192) (many KV splits per row, ragged last blocks), all 64 layers;
+    # the oracle follows the shortest and the longest sequence and two others
+    w = WORKLOADS["c5_62b_long"]
+    pos = synth.positions(w, "cpu").numpy()
+    rows = [int(np.argmin(pos)), int(np.argmax(pos)), 129, 7]
+    st, scaled, rel, _, _ = run_stack_parity(pd, w, rows=rows)
     assert scaled <= MAX_SCALED and rel <= REL_L2, (scaled, rel)
+    assert_bitwise_repeatable(st, st.x_out)
+    del st
+
+
+def _guarded(nbytes, fill):
+    """`nbytes` of device memory filled with byte `fill`, with 4 KiB canary bands on both sides."""
+    G = 4096
+    buf = torch.full((nbytes + 2 * G,), 0xA5, dtype=torch.uint8, device="cuda")
+    body = buf[G:G + nbytes]
+    body.fill_(fill)
+    assert body.data_ptr() % 256 == 0
+    return buf, body
+
+
+@pytest.mark.parametrize("shape", [
+    (3, 512, 5, 128, 384, 37, 160), (2, 1024, 32, 256, 1024, 70, 96), (2, 4096, 16, 256, 4096, 8, 512),
+])
+def test_poisoned_workspace_and_guard_bands(pd, shape):
+    # the step must write every workspace byte it later reads (the workspace arrives full
+    # of NaN bytes), and nothing outside the workspace and x_out (canaries on both sides)
+    from paper_2211_05102_amd import harness
+    L_, d, H, dh, F, B, L = shape
+    w = Workload("guard", L_, d, H, dh, F, B, L, positions="ragged", pos_lo=0, pos_hi=L)
+    st = harness.DeviceStack(w)
+    st.workspace.zero_()
+    want = st.step().clone()
+    st.dec.check_async(st.workspace)
+    G = 4096
+    for fill in (0xFF, 0x7F):
+        ws_buf, ws = _guarded(st.workspace.numel(), fill)
+        xo_buf, xo = _guarded(st.x_out.numel() * 2, fill)
+        st.dec.decode_step(st.packed, st.k_cache, st.v_cache, st.x_in, st.positions, w.l_ctx, xo, ws)
+        st.dec.check_async(ws)
+        for buf in (ws_buf, xo_buf):
+            assert int((buf[:G] != 0xA5).sum()) == 0 and int((buf[-G:] != 0xA5).sum()) == 0
+        assert torch.equal(xo.view(torch.int16).view(B, d), want.view(torch.int16))
 
 
 # ----------------------------------------------------- errors, graph replay ---
