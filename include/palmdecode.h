@@ -186,10 +186,31 @@ pd_status pd_decode_layer(pd_handle* h, int32_t layer, const void* packed_layer,
                           size_t workspace_bytes, void* stream);
 
 /* Synchronises `stream`, then reports the per-row position flags the most
- * recent step on this `workspace` left: PD_OK or PD_ERR_POSITION.
+ * recent step on this `workspace` left: PD_OK or PD_ERR_POSITION.  `workspace`
+ * NULL = the scratch of pd_decode_step_static() on the current device.
  * (Section 2.2: a step decodes the token at positions[b]; a position outside
  * the cache has no defined result.) */
 pd_status pd_check_async(pd_handle* h, void* workspace, void* stream);
+
+/*
+ * For callers that cannot allocate or pass device scratch: code under HIP graph
+ * capture that must not call an allocator, tight serving loops, harnesses that
+ * forbid allocation.  The same step as pd_decode_step() -- same kernels, same
+ * results bit for bit -- with the workspace taken from a fixed array inside the
+ * library's device image (64 MiB per GPU, held until the process ends) instead of
+ * from the caller.  Calls no allocator of any kind.  Shapes whose
+ * pd_workspace_bytes() exceeds 64 MiB are refused with PD_ERR_WORKSPACE and a
+ * message that says how much was needed; nothing is enqueued then.
+ * All calls on one GPU share that GPU's array: two calls whose execution overlaps
+ * on one GPU (different streams, or another thread) race; calls on one stream are
+ * ordered and safe.  The array needs no initial contents: every step writes what
+ * it later reads.  The device address of the array is looked up on the first
+ * call on each device (make that call before starting a stream capture).
+ * pd_check_async(h, NULL, stream) reads this step's position flags.
+ */
+pd_status pd_decode_step_static(pd_handle* h, const void* packed_weights, void* k_cache,
+                                void* v_cache, const uint16_t* x_in, const int32_t* positions,
+                                int32_t B, int32_t L_ctx, uint16_t* x_out, void* stream);
 
 /* ---- single steps of the path (tests, profiling) -------------------------- */
 

@@ -22,7 +22,7 @@ PD_ERR_WORKSPACE, PD_ERR_HIP, PD_ERR_POSITION, PD_ERR_STATE = -5, -6, -7, -8
 EXPORTS = [
     "pd_status_string", "pd_last_error", "pd_packed_layer_bytes", "pd_kv_cache_bytes",
     "pd_workspace_bytes", "pd_create", "pd_destroy", "pd_set_option", "pd_pack_layer",
-    "pd_pack_matrix", "pd_kv_import", "pd_kv_export", "pd_decode_step", "pd_decode_layer",
+    "pd_pack_matrix", "pd_kv_import", "pd_kv_export", "pd_decode_step", "pd_decode_step_static", "pd_decode_layer",
     "pd_check_async", "pd_qgemm_workspace_bytes", "pd_qgemm_plan", "pd_qgemm", "pd_mqa_attend",
     "pd_graph_capture", "pd_graph_replay", "pd_graph_release", "pd_profile_read",
 ]
@@ -192,6 +192,12 @@ class Decoder:
     def decode_step(self, packed, k_cache, v_cache, x_in, positions, L_ctx, x_out, workspace, stream=None) -> None:
         _check(lib().pd_decode_step(*self._step_args(packed, k_cache, v_cache, x_in, positions, L_ctx,
                                                      x_out, workspace, stream)))
+
+    def decode_step_static(self, packed, k_cache, v_cache, x_in, positions, L_ctx, x_out, stream=None) -> None:
+        B = x_in.shape[0]
+        _check(lib().pd_decode_step_static(self._h, _ptr(packed), _ptr(k_cache), _ptr(v_cache), _ptr(x_in),
+                                           _ptr(positions), ctypes.c_int32(B), ctypes.c_int32(L_ctx),
+                                           _ptr(x_out), _stream(stream)))
 
     def decode_layer(self, layer, packed_layer, k_cache, v_cache, x_in, positions, L_ctx, y_out,
                      add_residual, workspace, stream=None) -> None:

@@ -5,11 +5,19 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <mutex>
 #include <new>
 #include <vector>
 
 #include "../../include/palmdecode.h"
 #include "kernels.h"
+
+// Scratch memory of pd_decode_step_static(): one copy per GPU the library runs on, held
+// until the process ends.  In host code this name is only a stand-in for the symbol; the
+// device address comes from hipGetSymbolAddress (static_scratch() below) and that
+// pointer is what kernels and copies get.
+#define PD_STATIC_SCRATCH_BYTES (64u << 20)
+static __device__ __align__(256) unsigned char scratch[PD_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -305,6 +313,26 @@ pd_status run_layers(pd_handle* h, const StepArgs& a, hipStream_t st) {
     return PD_OK;
 }
 
+// Device address of `scratch` on the current device, looked up once per device.
+constexpr int PD_MAX_DEVICES = 64;
+unsigned char* g_scratch_ptr[PD_MAX_DEVICES];
+std::mutex g_scratch_mu;
+
+pd_status static_scratch(unsigned char** out) {
+    int dev = -1;
+    PD_TRY_HIP(hipGetDevice(&dev), "hipGetDevice");
+    if (dev < 0 || dev >= PD_MAX_DEVICES) return fail(PD_ERR_RANGE, "device index beyond the library's table");
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        PD_TRY_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)), "hipGetSymbolAddress(scratch)");
+        if (!p || !aligned(p, 256)) return fail(PD_ERR_HIP, "static scratch has no usable device address");
+        g_scratch_ptr[dev] = static_cast<unsigned char*>(p);
+    }
+    *out = g_scratch_ptr[dev];
+    return PD_OK;
+}
+
 pd_status check_step_args(pd_handle* h, const void* packed, void* kc, void* vc, const uint16_t* x_in,
                           const int32_t* positions, int32_t B, int32_t L_ctx, const void* out,
                           void* ws, size_t ws_bytes) {
@@ -507,6 +535,29 @@ pd_status pd_decode_step(pd_handle* h, const void* packed_weights, void* k_cache
     return run_layers(h, a, static_cast<hipStream_t>(stream));
 }
 
+pd_status pd_decode_step_static(pd_handle* h, const void* packed_weights, void* k_cache, void* v_cache,
+                                const uint16_t* x_in, const int32_t* positions, int32_t B, int32_t L_ctx,
+                                uint16_t* x_out, void* stream) {
+    if (!h) return fail(PD_ERR_NULL, "handle is NULL");
+    pd_status rc = check_batch(B, L_ctx);
+    if (rc != PD_OK) return rc;
+    if ((rc = check_limits(h->s, B)) != PD_OK) return rc;
+    const size_t need = workspace_layout(h->s, B, L_ctx).total;
+    if (need > PD_STATIC_SCRATCH_BYTES) {
+        snprintf(g_err, sizeof(g_err), "this shape needs %zu bytes of scratch; pd_decode_step_static holds %u "
+                 "(use pd_decode_step with a caller workspace)", need, PD_STATIC_SCRATCH_BYTES);
+        return PD_ERR_WORKSPACE;
+    }
+    unsigned char* ws = nullptr;
+    if ((rc = static_scratch(&ws)) != PD_OK) return rc;
+    rc = check_step_args(h, packed_weights, k_cache, v_cache, x_in, positions, B, L_ctx, x_out, ws,
+                         PD_STATIC_SCRATCH_BYTES);
+    if (rc != PD_OK) return rc;
+    StepArgs a{static_cast<const unsigned char*>(packed_weights), k_cache, v_cache, x_in, positions, B, L_ctx,
+               x_out, nullptr, 1, 0, h->s.L, ws};
+    return run_layers(h, a, static_cast<hipStream_t>(stream));
+}
+
 pd_status pd_decode_layer(pd_handle* h, int32_t layer, const void* packed_layer, void* k_cache,
                           void* v_cache, const uint16_t* x_in, const int32_t* positions, int32_t B,
                           int32_t L_ctx, float* y_out, int32_t add_residual, void* workspace,
@@ -521,7 +572,13 @@ pd_status pd_decode_layer(pd_handle* h, int32_t layer, const void* packed_layer,
 }
 
 pd_status pd_check_async(pd_handle* h, void* workspace, void* stream) {
-    if (!h || !workspace) return fail(PD_ERR_NULL, "NULL argument");
+    if (!h) return fail(PD_ERR_NULL, "NULL argument");
+    if (!workspace) {  // the step ran on the library's static scratch
+        unsigned char* ws = nullptr;
+        pd_status rc = static_scratch(&ws);
+        if (rc != PD_OK) return rc;
+        workspace = ws;
+    }
     hipStream_t st = static_cast<hipStream_t>(stream);
     PD_TRY_HIP(hipStreamSynchronize(st), "stream synchronize");
     int32_t flags[256];
