@@ -298,15 +298,24 @@ pd_status run_layers(pd_handle* h, const StepArgs& a, hipStream_t st) {
         prof_mark(h, PROF_QGEMM_OUT, st);
         const bool last = i == a.n_run - 1;
         prof_mark(h, PROF_EPI_OUT, st);
-        PD_TRY_HIP(pd::launch_residual(part_out, pl_out, s_out, xres, B, s.d, a.add_residual,
-                                       last ? a.x_out_bf16 : nullptr, last ? a.y_out_f32 : nullptr,
-                                       last ? nullptr : stats, st),
-                   "residual");
-        if (!last) {
+        if (!last && s.d <= PD_RESIDUAL_LN_MAX_D) {
+            // the updated row stays in one workgroup's registers from the residual add to the
+            // next layer's LayerNorm
             const unsigned char* Ln = L + pl.total;
-            PD_TRY_HIP(pd::launch_ln_slices(xres, reinterpret_cast<const float*>(Ln + pl.gamma),
-                                            reinterpret_cast<const float*>(Ln + pl.gamma_absmax), stats, B, s.d,
-                                            h->desc.ln_eps, hq, hs, nd, st), "ln");
+            PD_TRY_HIP(pd::launch_residual_ln(part_out, pl_out, s_out, xres, B, s.d, a.add_residual,
+                                              reinterpret_cast<const float*>(Ln + pl.gamma), h->desc.ln_eps,
+                                              hq, hs, nd, st), "residual + ln");
+        } else {
+            PD_TRY_HIP(pd::launch_residual(part_out, pl_out, s_out, xres, B, s.d, a.add_residual,
+                                           last ? a.x_out_bf16 : nullptr, last ? a.y_out_f32 : nullptr,
+                                           last ? nullptr : stats, st),
+                       "residual");
+            if (!last) {
+                const unsigned char* Ln = L + pl.total;
+                PD_TRY_HIP(pd::launch_ln_slices(xres, reinterpret_cast<const float*>(Ln + pl.gamma),
+                                                reinterpret_cast<const float*>(Ln + pl.gamma_absmax), stats, B, s.d,
+                                                h->desc.ln_eps, hq, hs, nd, st), "ln");
+            }
         }
         prof_mark(h, PROF_EPI_OUT, st);
     }

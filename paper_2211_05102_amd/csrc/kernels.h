@@ -49,6 +49,12 @@ hipError_t launch_residual(const float* part, SkqPlan pl, const float* scale, fl
 hipError_t launch_ln_slices(const float* xres, const float* gamma, const float* gamma_absmax,
                             const float* stats, int B, int d, float eps, void* hq, float* hs,
                             int nd, hipStream_t stream);
+// residual add + LayerNorm of the next layer in one launch; rows of at most
+// PD_RESIDUAL_LN_MAX_D columns
+#define PD_RESIDUAL_LN_MAX_D 16384
+hipError_t launch_residual_ln(const float* part, SkqPlan pl, const float* scale, float* xres, int B,
+                              int d, int add_residual, const float* gamma, float eps, void* hq, float* hs,
+                              int nd, hipStream_t stream);
 hipError_t launch_vec_absmax(const float* v, int n, float* out, hipStream_t stream);
 
 }  // namespace pd

@@ -287,6 +287,133 @@ __global__ __launch_bounds__(256) void ln_slices_kernel(const float* __restrict_
     }
 }
 
+// ---- residual add and the next layer's LayerNorm in one kernel ------------------
+// One workgroup of 1024 threads per batch row, for rows of at most 16384 columns: the
+// updated row stays in registers between the residual add and the LayerNorm, mean and
+// variance are the exact two-pass ones and the row's power-of-two scale comes from the
+// exact maximum.  Sums over the 16 waves go through LDS in wave order (fixed order).
+constexpr int RL_THREADS = 1024;
+constexpr int RL_MAXQ = 4;  // f32x4 groups per thread: rows of up to 1024 * 4 * 4 columns (more would spill)
+
+__device__ __forceinline__ float block_sum_1024(float v, float* red) {
+    v = wave_sum(v);
+    __syncthreads();  // protects `red` against the previous use
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+    __syncthreads();
+    float t = 0.f;
+#pragma unroll
+    for (int w = 0; w < RL_THREADS / 64; w++) t += red[w];
+    return t;
+}
+__device__ __forceinline__ float block_max_1024(float v, float* red) {
+    v = wave_max(v);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+    __syncthreads();
+    float t = red[0];
+#pragma unroll
+    for (int w = 1; w < RL_THREADS / 64; w++) t = fmaxf(t, red[w]);
+    return t;
+}
+
+// digits of four consecutive elements c .. c + 3 of a row (c % 4 == 0) into the chunk
+// that holds them; plane p of chunk j sits at j * 128 * nd + 128 * p (see common.h)
+__device__ __forceinline__ void quantize_quad_store(const f32x4 v, float inv_scale, int nd, int c,
+                                                    unsigned char* __restrict__ row) {
+    const int lim = 127 << (8 * (nd - 1));
+    int n[4];
+#pragma unroll
+    for (int k = 0; k < 4; k++) {
+        n[k] = (int)rintf(v[k] * inv_scale);
+        n[k] = n[k] > lim ? lim : (n[k] < -lim ? -lim : n[k]);
+    }
+    unsigned char* chunk = row + (size_t)(c >> 7) * QCHUNK * nd + (c & 127);
+    for (int p = nd - 1; p >= 0; p--) {
+        uint32_t word = 0;
+#pragma unroll
+        for (int k = 0; k < 4; k++) {
+            int d;
+            if (p > 0) {
+                const int h = (n[k] + 128) >> 8;  // floor division keeps every lower digit in [-128, 127]
+                d = n[k] - (h << 8);
+                n[k] = h;
+            } else {
+                d = n[k];
+            }
+            word |= (uint32_t)(d & 0xff) << (8 * k);
+        }
+        store_through(reinterpret_cast<uint32_t*>(chunk + p * QCHUNK), word);
+    }
+}
+
+template <int NQ>  // f32x4 groups per thread
+__global__ __launch_bounds__(RL_THREADS) void residual_ln_kernel(
+    const float* __restrict__ part, SkqPlan pl, const float* __restrict__ scale,
+    float* __restrict__ xres, int d, int add_residual, const float* __restrict__ gamma, float eps,
+    unsigned char* __restrict__ hq, float* __restrict__ hs, int nd) {
+    __shared__ float red[RL_THREADS / 64];
+    const int tid = threadIdx.x, b = blockIdx.x;
+    const size_t stride = (size_t)pl.rows * d, rowoff = (size_t)b * d;
+    f32x4 xn[NQ];
+    float sum = 0.f;
+#pragma unroll
+    for (int i = 0; i < NQ; i++) {
+        const int c = (i * RL_THREADS + tid) * 4;
+        xn[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
+        if (c < d) {
+            const int ns = pl.nseg[c / pl.tile_cols];  // 4 columns share a tile
+            // slots are added in index order; four loads are in flight at a time (a slot index
+            // past the last one re-reads the last slot and is not added)
+            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+            for (int s0 = 0; s0 < ns; s0 += 4) {
+                f32x4 pv[4];
+#pragma unroll
+                for (int k = 0; k < 4; k++) {
+                    const int sk = s0 + k < ns ? s0 + k : ns - 1;
+                    pv[k] = *reinterpret_cast<const f32x4*>(part + (size_t)sk * stride + rowoff + c);
+                }
+#pragma unroll
+                for (int k = 0; k < 4; k++)
+                    if (s0 + k < ns) acc += pv[k];
+            }
+            f32x4 v = *reinterpret_cast<const f32x4*>(scale + c) * acc;
+            if (add_residual) v += *reinterpret_cast<const f32x4*>(xres + rowoff + c);
+            *reinterpret_cast<f32x4*>(xres + rowoff + c) = v;
+            xn[i] = v;
+            sum += (v.x + v.y) + (v.z + v.w);
+        }
+    }
+    const float mean = block_sum_1024(sum, red) / (float)d;
+    float sq = 0.f;
+#pragma unroll
+    for (int i = 0; i < NQ; i++) {
+        const int c = (i * RL_THREADS + tid) * 4;
+        if (c < d) {
+            xn[i] -= mean;
+            sq += (xn[i].x * xn[i].x + xn[i].y * xn[i].y) + (xn[i].z * xn[i].z + xn[i].w * xn[i].w);
+        }
+    }
+    const float rstd = 1.0f / sqrtf(block_sum_1024(sq, red) / (float)d + eps);
+    float mx = 0.f;
+#pragma unroll
+    for (int i = 0; i < NQ; i++) {
+        const int c = (i * RL_THREADS + tid) * 4;
+        if (c < d) xn[i] = *reinterpret_cast<const f32x4*>(gamma + c) * xn[i] * rstd;  // (zero beyond the row)
+        mx = fmaxf(mx, fmaxf(fmaxf(fabsf(xn[i].x), fabsf(xn[i].y)), fmaxf(fabsf(xn[i].z), fabsf(xn[i].w))));
+    }
+    const float s = qscale_from_max(block_max_1024(mx, red), nd);
+    const float inv = 1.0f / s;
+    unsigned char* hrow = hq + rowoff * nd;
+#pragma unroll
+    for (int i = 0; i < NQ; i++) {
+        const int c = (i * RL_THREADS + tid) * 4;
+        if (c < d) {
+            quantize_quad_store(xn[i], inv, nd, c, hrow);
+            if ((c & 127) == 0) hs[(size_t)(c >> 7) * QSCALE_ROWS + b] = s;
+        }
+    }
+}
+
 // max |v[i]| of an fp32 vector (pack time: the LayerNorm gain of a layer)
 __global__ __launch_bounds__(256) void vec_absmax_kernel(const float* __restrict__ v, int n,
                                                          float* __restrict__ out) {
@@ -338,6 +465,20 @@ hipError_t launch_ln_slices(const float* xres, const float* gamma, const float* 
                             int nd, hipStream_t stream) {
     ln_slices_kernel<<<dim3((d + 1023) / 1024, B), dim3(256), 0, stream>>>(
         xres, gamma, gamma_absmax, stats, d, eps, reinterpret_cast<unsigned char*>(hq), hs, nd);
+    return hipGetLastError();
+}
+
+hipError_t launch_residual_ln(const float* part, SkqPlan pl, const float* scale, float* xres, int B,
+                              int d, int add_residual, const float* gamma, float eps, void* hq, float* hs,
+                              int nd, hipStream_t stream) {
+    if (d > RL_THREADS * 4 * RL_MAXQ) return hipErrorInvalidValue;
+    const int nq = (d + RL_THREADS * 4 - 1) / (RL_THREADS * 4);
+    unsigned char* q = reinterpret_cast<unsigned char*>(hq);
+#define PD_RL(NQ) residual_ln_kernel<NQ><<<dim3(B), dim3(RL_THREADS), 0, stream>>>(part, pl, scale, xres, d, add_residual, gamma, eps, q, hs, nd)
+    if (nq <= 1) PD_RL(1);
+    else if (nq <= 2) PD_RL(2);
+    else PD_RL(4);
+#undef PD_RL
     return hipGetLastError();
 }
 
