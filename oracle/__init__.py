@@ -48,6 +48,7 @@ def lib():
         _lib.orc_f64_to_bf16.argtypes = [ctypes.c_double]
         _lib.orc_num_threads.restype = ctypes.c_int
         _lib.orc_decode_layer.restype = ctypes.c_int
+        _lib.orc_sample_topk_topp.restype = ctypes.c_int
         _lib.orc_causal_layer.restype = ctypes.c_int
     return _lib
 
@@ -144,6 +145,34 @@ def swiglu(g: np.ndarray, u: np.ndarray) -> np.ndarray:
     lib().orc_swiglu(_p(g, np.float64), _p(u, np.float64), ctypes.c_int32(g.shape[0]),
                      _p(a, np.float64))
     return a
+
+
+def head_logits(x: np.ndarray, gamma_f_bits: np.ndarray, w_vocab: np.ndarray, s_vocab_bits: np.ndarray,
+                eps: float) -> np.ndarray:
+    """Final LayerNorm + vocabulary projection: x [R, d] fp64 -> logits [R, V] fp64."""
+    x = np.ascontiguousarray(x, dtype=np.float64)
+    R, d = x.shape
+    w = _i8(w_vocab)
+    V = w.shape[1]
+    assert w.shape == (d, V)
+    out = np.empty((R, V), dtype=np.float64)
+    lib().orc_head_logits(_p(x, np.float64), _p(_bits(gamma_f_bits), np.uint16), _p(w, np.int8),
+                          _p(_bits(s_vocab_bits), np.uint16), ctypes.c_int32(R), ctypes.c_int32(d),
+                          ctypes.c_int32(V), ctypes.c_double(eps), _p(out, np.float64))
+    return out
+
+
+def sample_topk_topp(logits: np.ndarray, k: int, top_p: float, temperature: float, u: float):
+    """One token from logits [V]: returns (token, kept entries, margin of the draw)."""
+    logits = np.ascontiguousarray(logits, dtype=np.float64)
+    assert logits.ndim == 1
+    tok, kept, margin = ctypes.c_int32(-1), ctypes.c_int32(0), ctypes.c_double(0.0)
+    rc = lib().orc_sample_topk_topp(_p(logits, np.float64), ctypes.c_int32(logits.shape[0]), ctypes.c_int32(k),
+                                    ctypes.c_double(top_p), ctypes.c_double(temperature), ctypes.c_double(u),
+                                    ctypes.byref(tok), ctypes.byref(kept), ctypes.byref(margin))
+    if rc != 0:
+        raise ValueError("oracle sample_topk_topp: bad argument")
+    return tok.value, kept.value, margin.value
 
 
 # ------------------------------------------------------------------ layers ---

@@ -280,6 +280,87 @@ int orc_decode_layer(const orc_desc* m, const int8_t* w_in, const uint16_t* s_in
     return 0;
 }
 
+/* --------------------------------------------------- sampling head (f1) --- */
+
+/*
+ * The tail of a generation step (Section 2.2: after the forward pass one new
+ * token is sampled for each sequence): final LayerNorm of the hidden state,
+ * logits = LN(x) . deq(W_vocab) with the same weight-only int8 format as the
+ * other matrices (Section 3.6).  The paper gives no formula for this tail (the
+ * model is PaLM's by citation); the reading is: the same LayerNorm as in the
+ * blocks with its own gain, no bias, a [d][V] int8 matrix with one bf16 scale
+ * per vocabulary entry.
+ * x: [R][d] fp64 hidden state, logits: [R][V] fp64.
+ */
+void orc_head_logits(const double* x, const uint16_t* gamma_f, const int8_t* w_vocab,
+                     const uint16_t* s_vocab, int32_t R, int32_t d, int32_t V, double eps,
+                     double* logits) {
+    double* h = (double*)malloc((size_t)R * d * sizeof(double));
+    for (int32_t r = 0; r < R; r++) orc_layernorm(x + (size_t)r * d, gamma_f, d, eps, h + (size_t)r * d);
+    orc_qmatmul(h, w_vocab, s_vocab, R, d, V, logits);
+    free(h);
+}
+
+/*
+ * Top-k / top-p (nucleus) sampling of ONE token from `logits` [V] (Section 3.5
+ * names top-k/top-p decode sampling; the definition written out here is the usual
+ * one):
+ *   1. order the vocabulary by logit, largest first, equal logits by smaller index;
+ *   2. keep the first k entries;
+ *   3. p_i = softmax(logit_i / temperature) over the kept entries;
+ *   4. keep the shortest prefix whose probabilities sum to at least top_p (at least
+ *      one entry);
+ *   5. with c_i the running sums over that prefix and c_n its total, return the first
+ *      entry with c_i > u * c_n, u in [0, 1) supplied by the caller (the last entry
+ *      if rounding leaves none).
+ * The random number is an input: the method's random draws do not live here.
+ * Plain selection sort of the first k entries: O(k V), obviously correct.
+ * Outputs: *token; optionally kept[0] = entries that survived step 4 and
+ * margin[0] = distance of u * c_n from the nearest boundary of the chosen entry's
+ * interval, relative to c_n (how well-conditioned the draw is).
+ * Returns 0, or -1 on a bad argument.
+ */
+int orc_sample_topk_topp(const double* logits, int32_t V, int32_t k, double top_p,
+                         double temperature, double u, int32_t* token, int32_t* kept,
+                         double* margin) {
+    if (V < 1 || k < 1 || k > V || !(top_p > 0.0) || top_p > 1.0 || !(temperature > 0.0) ||
+        !(u >= 0.0) || !(u < 1.0))
+        return -1;
+    int32_t* idx = (int32_t*)malloc((size_t)k * sizeof(int32_t));
+    double* pr = (double*)malloc((size_t)k * sizeof(double));
+    char* taken = (char*)calloc((size_t)V, 1);
+    for (int32_t i = 0; i < k; i++) { /* i-th largest, ties by smaller index */
+        int32_t best = -1;
+        for (int32_t v = 0; v < V; v++) {
+            if (taken[v]) continue;
+            if (best < 0 || logits[v] > logits[best]) best = v;
+        }
+        taken[best] = 1;
+        idx[i] = best;
+    }
+    double m = logits[idx[0]] / temperature, z = 0.0;
+    for (int32_t i = 0; i < k; i++) { pr[i] = exp(logits[idx[i]] / temperature - m); z += pr[i]; }
+    for (int32_t i = 0; i < k; i++) pr[i] /= z;
+    int32_t n = 0;
+    double c = 0.0;
+    while (n < k) { c += pr[n]; n++; if (c >= top_p) break; }
+    double target = u * c, run = 0.0, lo = 0.0;
+    int32_t pick = n - 1;
+    for (int32_t i = 0; i < n; i++) {
+        lo = run;
+        run += pr[i];
+        if (run > target) { pick = i; break; }
+    }
+    *token = idx[pick];
+    if (kept) *kept = n;
+    if (margin) {
+        double a = target - lo, b = run - target;
+        *margin = (a < b ? a : b) / c;
+    }
+    free(idx); free(pr); free(taken);
+    return 0;
+}
+
 /* --------------------------------------------- full causal forward (pins) --- */
 
 /*

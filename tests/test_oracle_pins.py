@@ -437,3 +437,117 @@ def test_synthetic_streams_are_reproducible_and_independent():
     p = synth.positions(WORKLOADS["c5_62b_long"])
     assert p.shape == (256,) and int(p.min()) >= 4096 and int(p.max()) < 8192
     assert torch.equal(p, synth.positions(WORKLOADS["c5_62b_long"]))
+
+
+# ------------------------------------------------- sampling head (Section 2.2) ---
+
+def _np_sample(logits, k, top_p, temperature, u):
+    """The same definition through numpy's library routines (stable argsort, cumsum,
+    searchsorted): an independent route to the token."""
+    order = np.argsort(-logits, kind="stable")[:k]          # largest first, ties by smaller index
+    z = logits[order] / temperature
+    p = np.exp(z - z.max())
+    p /= p.sum()
+    c = np.cumsum(p)
+    n = int(np.searchsorted(c, top_p, side="left")) + 1       # shortest prefix with sum >= top_p
+    n = min(n, k)
+    c = np.cumsum(p[:n])
+    i = int(np.searchsorted(c, u * c[-1], side="right"))     # first entry with running sum > target
+    return int(order[min(i, n - 1)]), n
+
+
+def test_sampler_vs_numpy_sort_and_cumsum():
+    rng = np.random.default_rng(17)
+    checked = 0
+    for trial in range(300):
+        V = int(rng.integers(1, 400))
+        k = int(rng.integers(1, min(V, 64) + 1))
+        top_p = float(rng.uniform(0.05, 1.0))
+        T = float(rng.uniform(0.2, 2.0))
+        u = float(rng.uniform(0, 1))
+        logits = rng.standard_normal(V) * 3
+        if trial % 5 == 0:
+            logits = np.round(logits)  # many exact ties
+        tok, kept, margin = oracle.sample_topk_topp(logits, k, top_p, T, u)
+        want, n = _np_sample(logits, k, top_p, T, u)
+        if margin > 1e-9:  # away from an interval boundary the two routes must agree exactly
+            assert (tok, kept) == (want, n), (trial, V, k, top_p, T, u)
+            checked += 1
+    assert checked > 280
+
+
+def test_sampler_degenerate_cases_are_argmax():
+    rng = np.random.default_rng(3)
+    logits = rng.standard_normal(1000)
+    logits[[100, 700]] = logits.max() + 1.0  # tie for the maximum: the smaller index wins
+    for u in (0.0, 0.3, 0.999999):
+        assert oracle.sample_topk_topp(logits, 1, 1.0, 1.0, u)[0] == 100          # k = 1
+        assert oracle.sample_topk_topp(logits, 50, 1e-9, 1.0, u)[:2] == (100, 1)  # top_p -> 0
+    logits[700] -= 0.5
+    for u in (0.0, 0.5, 0.99):
+        assert oracle.sample_topk_topp(logits, 50, 1.0, 1e-3, u)[0] == 100        # temperature -> 0
+
+
+def test_sampler_uniform_logits_invert_the_uniform_cdf():
+    V = 37
+    logits = np.full(V, 1.25)
+    for u in np.linspace(0.0, 0.999, 101):
+        tok, kept, _ = oracle.sample_topk_topp(logits, V, 1.0, 0.7, float(u))
+        frac = u * V
+        if abs(frac - round(frac)) > 1e-9:
+            assert tok == int(math.floor(frac)) and kept == V
+
+
+def test_sampler_two_tokens_closed_form_and_temperature():
+    a, b = 0.3, 1.1
+    for T in (0.5, 1.0, 2.0):
+        p_b = 1.0 / (1.0 + math.exp((a - b) / T))  # larger logit comes first in the order
+        for u in np.linspace(0.001, 0.999, 200):
+            tok = oracle.sample_topk_topp(np.array([a, b]), 2, 1.0, T, float(u))[0]
+            if abs(u - p_b) > 1e-9:
+                assert tok == (1 if u < p_b else 0), (T, u)
+
+
+def test_sampler_nucleus_keeps_the_shortest_prefix_and_renormalises():
+    logits = np.log(np.array([0.2, 0.5, 0.3]))
+    assert oracle.sample_topk_topp(logits, 3, 0.79, 1.0, 0.1)[1] == 2  # 0.5 + 0.3 reaches 0.79
+    assert oracle.sample_topk_topp(logits, 3, 0.81, 1.0, 0.1)[1] == 3
+    assert oracle.sample_topk_topp(logits, 3, 0.49, 1.0, 0.1)[1] == 1
+    # inside the nucleus {0.5, 0.3} the draw uses the renormalised 0.625 / 0.375
+    assert oracle.sample_topk_topp(logits, 3, 0.79, 1.0, 0.62)[0] == 1
+    assert oracle.sample_topk_topp(logits, 3, 0.79, 1.0, 0.63)[0] == 2
+    # top-k cuts before top-p
+    assert oracle.sample_topk_topp(logits, 1, 1.0, 1.0, 0.99)[:2] == (1, 1)
+
+
+def test_sampler_frequencies_follow_the_softmax():
+    rng = np.random.default_rng(5)
+    logits = rng.standard_normal(12)
+    T, N = 0.8, 20000
+    counts = np.zeros(12)
+    for i in range(N):
+        counts[oracle.sample_topk_topp(logits, 12, 1.0, T, (i + 0.5) / N)[0]] += 1
+    p = np.exp(logits / T)
+    p /= p.sum()
+    assert np.max(np.abs(counts / N - p)) <= 1.5 / N * 12  # each interval end moves the count by at most one
+
+
+def test_sampler_rejects_bad_arguments():
+    for bad in ((0, 1.0, 1.0, 0.5), (4, 1.0, 1.0, 0.5), (1, 0.0, 1.0, 0.5), (1, 1.0, 0.0, 0.5), (1, 1.0, 1.0, 1.0)):
+        with pytest.raises(ValueError):
+            oracle.sample_topk_topp(np.zeros(3), *bad)
+
+
+def test_head_logits_are_layernorm_then_projection():
+    rng = np.random.default_rng(9)
+    R, d, V = 3, 96, 50
+    x = rng.standard_normal((R, d)) * 7 + 0.3
+    gamma = torch.tensor(1 + 0.05 * rng.standard_normal(d)).to(torch.bfloat16)
+    w = torch.tensor(rng.integers(-127, 128, (d, V)), dtype=torch.int8)
+    s = torch.tensor(rng.uniform(1e-3, 2e-3, V)).to(torch.bfloat16)
+    got = oracle.head_logits(x, gamma, w, s, 1e-6)
+    g64, s64 = gamma.double().numpy(), s.double().numpy()
+    mu = x.mean(axis=1, keepdims=True)
+    h = g64 * (x - mu) / np.sqrt(((x - mu) ** 2).mean(axis=1, keepdims=True) + 1e-6)
+    want = (h @ w.double().numpy()) * s64
+    assert np.max(np.abs(got - want)) <= 1e-12 * np.max(np.abs(want))
