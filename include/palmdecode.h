@@ -249,6 +249,65 @@ pd_status pd_mqa_attend(pd_handle* h, int32_t layer, const float* q, const void*
                         const void* v_cache, const int32_t* positions, int32_t B, int32_t L_ctx,
                         float* o, void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---- sampling head and the generation loop --------------------------------
+ * Section 2.2: generation is a sequential loop of L_gen steps; each step is one
+ * forward pass after which one new token is sampled for each of the B sequences
+ * and fed back.  Section 3.5 names fast top-k / top-p sampling for decode.  The
+ * model tail is PaLM's by citation; the reading used here: a final LayerNorm
+ * (same definition as in the blocks, own gain), logits = LN(x) . W_vocab with
+ * W_vocab [d_model][vocab] int8 + one bf16 scale per vocabulary entry (the format
+ * of Section 3.6), and the next input = row `token` of an embedding table
+ * [vocab][d_model] bf16.
+ *
+ * Sampling of one row (fp32): order the vocabulary by logit, largest first, equal
+ * logits by smaller index; keep the first top_k (1..64); p = softmax(logit /
+ * temperature) over them; keep the shortest prefix whose mass reaches top_p; with
+ * c_i the running sums over that prefix and c_n its total, the token is the first
+ * entry with c_i > u * c_n (u in [0,1) supplied by the caller: the library draws
+ * no random numbers).  Logits must be finite.
+ */
+
+/* Bytes of the packed head (vocab % 32 == 0, d_model * vocab < 4 GiB). */
+pd_status pd_packed_head_bytes(const pd_model_desc* desc, int32_t vocab, size_t* bytes);
+/* Scratch of pd_head_logits() for batch B. */
+pd_status pd_head_workspace_bytes(const pd_model_desc* desc, int32_t vocab, int32_t B, size_t* bytes);
+/* Scratch of pd_generate() for batch B and cache capacity L_ctx (includes the
+ * decode step's and the head's). */
+pd_status pd_generate_workspace_bytes(const pd_model_desc* desc, int32_t vocab, int32_t B, int32_t L_ctx,
+                                      size_t* bytes);
+/* Canonical device tensors -> packed head: w_vocab [d_model][vocab] int8 row-major,
+ * s_vocab [vocab] bf16, gamma_f [d_model] bf16. */
+pd_status pd_pack_head(pd_handle* h, const int8_t* w_vocab, const uint16_t* s_vocab,
+                       const uint16_t* gamma_f, int32_t vocab, void* packed_head, void* stream);
+/* logits [B][vocab] fp32 (device) = LN_f(x) . deq(W_vocab) for x [B][d_model] bf16. */
+pd_status pd_head_logits(pd_handle* h, const void* packed_head, int32_t vocab, const uint16_t* x,
+                         int32_t B, float* logits, void* workspace, size_t workspace_bytes,
+                         void* stream);
+/* tokens[b] (device int32) = the draw defined above from logits [B][vocab] fp32
+ * with uniforms[b] (device fp32 in [0,1)).  Bit-reproducible. */
+pd_status pd_sample(const float* logits, int32_t B, int32_t vocab, int32_t top_k, float top_p,
+                    float temperature, const float* uniforms, int32_t* tokens, void* stream);
+/*
+ * n_steps generation steps.  Per step i: one decode step of the stack on x at
+ * positions (K/V appended as in pd_decode_step), logits, one draw per row with
+ * uniforms[i][b], tokens_out[i][b] = the token, x[b] = embed[token], positions[b]
+ * += 1.  Everything advances on the device; with use_graph != 0 one step is
+ * captured as a HIP graph (owned by the handle) and replayed n_steps times.
+ *   x              device [B][d_model] bf16, in: hidden state (embedding) of the
+ *                  current token of each sequence; out: embedding of the last draw
+ *   positions      device [B] int32, in/out; positions[b] + n_steps <= L_ctx is the
+ *                  caller's duty (a row that runs past L_ctx is flagged as in
+ *                  pd_decode_step and reported by pd_check_async(h, workspace, ..))
+ *   uniforms       device [n_steps][B] fp32;  tokens_out device [n_steps][B] int32
+ *   workspace      device, >= pd_generate_workspace_bytes()
+ */
+pd_status pd_generate(pd_handle* h, const void* packed_weights, const void* packed_head,
+                      const uint16_t* embed, void* k_cache, void* v_cache, uint16_t* x,
+                      int32_t* positions, int32_t B, int32_t L_ctx, int32_t vocab, int32_t n_steps,
+                      int32_t top_k, float top_p, float temperature, const float* uniforms,
+                      int32_t* tokens_out, int32_t use_graph, void* workspace,
+                      size_t workspace_bytes, void* stream);
+
 /* ---- graph replay ---------------------------------------------------------
  * Section 2.2: generation repeats the same step once per token; replaying a
  * captured step removes the per-kernel launch cost from that loop. */

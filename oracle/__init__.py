@@ -156,8 +156,10 @@ def head_logits(x: np.ndarray, gamma_f_bits: np.ndarray, w_vocab: np.ndarray, s_
     V = w.shape[1]
     assert w.shape == (d, V)
     out = np.empty((R, V), dtype=np.float64)
-    lib().orc_head_logits(_p(x, np.float64), _p(_bits(gamma_f_bits), np.uint16), _p(w, np.int8),
-                          _p(_bits(s_vocab_bits), np.uint16), ctypes.c_int32(R), ctypes.c_int32(d),
+    gamma, scales = _bits(gamma_f_bits), _bits(s_vocab_bits)  # (kept alive across the call)
+    assert gamma.shape == (d,) and scales.shape == (V,)
+    lib().orc_head_logits(_p(x, np.float64), _p(gamma, np.uint16), _p(w, np.int8),
+                          _p(scales, np.uint16), ctypes.c_int32(R), ctypes.c_int32(d),
                           ctypes.c_int32(V), ctypes.c_double(eps), _p(out, np.float64))
     return out
 

@@ -25,6 +25,8 @@ EXPORTS = [
     "pd_pack_matrix", "pd_kv_import", "pd_kv_export", "pd_decode_step", "pd_decode_step_static", "pd_decode_layer",
     "pd_check_async", "pd_qgemm_workspace_bytes", "pd_qgemm_plan", "pd_qgemm", "pd_mqa_attend",
     "pd_graph_capture", "pd_graph_replay", "pd_graph_release", "pd_profile_read",
+    "pd_packed_head_bytes", "pd_head_workspace_bytes", "pd_generate_workspace_bytes", "pd_pack_head",
+    "pd_head_logits", "pd_sample", "pd_generate",
 ]
 
 
@@ -118,6 +120,35 @@ def qgemm_plan(B: int, K: int, N: int, workgroups: int = 0, c_split: int = 0, bl
     _check(lib().pd_qgemm_plan(*args, counts, rb, fs, spt))
     names = ("workgroups", "tiles", "chunks_per_tile", "rows", "max_slots")
     return dict(zip(names, list(counts))), list(rb), list(fs), list(spt)
+
+
+def packed_head_bytes(desc: ModelDesc, vocab: int) -> int:
+    n = ctypes.c_size_t(0)
+    _check(lib().pd_packed_head_bytes(ctypes.byref(desc), ctypes.c_int32(vocab), ctypes.byref(n)))
+    return n.value
+
+
+def head_workspace_bytes(desc: ModelDesc, vocab: int, B: int) -> int:
+    n = ctypes.c_size_t(0)
+    _check(lib().pd_head_workspace_bytes(ctypes.byref(desc), ctypes.c_int32(vocab), ctypes.c_int32(B), ctypes.byref(n)))
+    return n.value
+
+
+def generate_workspace_bytes(desc: ModelDesc, vocab: int, B: int, L_ctx: int) -> int:
+    n = ctypes.c_size_t(0)
+    _check(lib().pd_generate_workspace_bytes(ctypes.byref(desc), ctypes.c_int32(vocab), ctypes.c_int32(B),
+                                             ctypes.c_int32(L_ctx), ctypes.byref(n)))
+    return n.value
+
+
+def sample(logits: torch.Tensor, top_k: int, top_p: float, temperature: float, uniforms: torch.Tensor,
+           tokens: torch.Tensor, stream=None) -> None:
+    B, V = logits.shape
+    assert logits.dtype == torch.float32 and logits.is_contiguous() and uniforms.dtype == torch.float32
+    assert tokens.dtype == torch.int32 and tokens.numel() >= B and uniforms.numel() >= B
+    _check(lib().pd_sample(_ptr(logits), ctypes.c_int32(B), ctypes.c_int32(V), ctypes.c_int32(top_k),
+                           ctypes.c_float(top_p), ctypes.c_float(temperature), _ptr(uniforms), _ptr(tokens),
+                           _stream(stream)))
 
 
 def pack_matrix(w: torch.Tensor, packed: torch.Tensor, stream=None) -> None:
@@ -220,6 +251,27 @@ class Decoder:
                                    _ptr(workspace),
                                    ctypes.c_size_t(workspace.numel() * workspace.element_size()),
                                    _stream(stream)))
+
+    def pack_head(self, w_vocab, s_vocab, gamma_f, packed_head, stream=None) -> None:
+        vocab = w_vocab.shape[1]
+        _check(lib().pd_pack_head(self._h, _ptr(w_vocab), _ptr(s_vocab), _ptr(gamma_f), ctypes.c_int32(vocab),
+                                  _ptr(packed_head), _stream(stream)))
+
+    def head_logits(self, packed_head, vocab, x, logits, workspace, stream=None) -> None:
+        B = x.shape[0]
+        _check(lib().pd_head_logits(self._h, _ptr(packed_head), ctypes.c_int32(vocab), _ptr(x), ctypes.c_int32(B),
+                                    _ptr(logits), _ptr(workspace),
+                                    ctypes.c_size_t(workspace.numel() * workspace.element_size()), _stream(stream)))
+
+    def generate(self, packed, packed_head, embed, k_cache, v_cache, x, positions, L_ctx, vocab, n_steps,
+                 top_k, top_p, temperature, uniforms, tokens_out, use_graph, workspace, stream=None) -> None:
+        B = x.shape[0]
+        _check(lib().pd_generate(self._h, _ptr(packed), _ptr(packed_head), _ptr(embed), _ptr(k_cache), _ptr(v_cache),
+                                 _ptr(x), _ptr(positions), ctypes.c_int32(B), ctypes.c_int32(L_ctx),
+                                 ctypes.c_int32(vocab), ctypes.c_int32(n_steps), ctypes.c_int32(top_k),
+                                 ctypes.c_float(top_p), ctypes.c_float(temperature), _ptr(uniforms),
+                                 _ptr(tokens_out), ctypes.c_int32(int(use_graph)), _ptr(workspace),
+                                 ctypes.c_size_t(workspace.numel() * workspace.element_size()), _stream(stream)))
 
     def graph_capture(self, packed, k_cache, v_cache, x_in, positions, L_ctx, x_out, workspace, stream) -> None:
         _check(lib().pd_graph_capture(*self._step_args(packed, k_cache, v_cache, x_in, positions, L_ctx,

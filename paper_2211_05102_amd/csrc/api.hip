@@ -197,6 +197,8 @@ struct pd_handle {
     int act_digits = 3;  // int8 digit planes per projection operand
     hipGraph_t graph = nullptr;
     hipGraphExec_t graph_exec = nullptr;
+    hipGraph_t gen_graph = nullptr;  // one iteration of pd_generate
+    hipGraphExec_t gen_exec = nullptr;
     // optional event timing of one kernel class (0 = off), see pd_profile_read
     int profile_kernel = 0;
     std::vector<hipEvent_t> ev_pool;  // pairs: start, stop
@@ -427,6 +429,8 @@ pd_status pd_graph_release(pd_handle* h) {
     if (!h) return fail(PD_ERR_NULL, "handle is NULL");
     if (h->graph_exec) { (void)hipGraphExecDestroy(h->graph_exec); h->graph_exec = nullptr; }
     if (h->graph) { (void)hipGraphDestroy(h->graph); h->graph = nullptr; }
+    if (h->gen_exec) { (void)hipGraphExecDestroy(h->gen_exec); h->gen_exec = nullptr; }
+    if (h->gen_graph) { (void)hipGraphDestroy(h->gen_graph); h->gen_graph = nullptr; }
     return PD_OK;
 }
 
@@ -700,6 +704,233 @@ pd_status pd_mqa_attend(pd_handle* h, int32_t layer, const float* q, const void*
                                      s.dh, L_ctx, bps, reinterpret_cast<float*>(ws + w.opart),
                                      reinterpret_cast<float*>(ws + w.ml), o, nullptr, nullptr, s.k_out, 1,
                                      h->act_digits, static_cast<hipStream_t>(stream)), "mqa_attend");
+    return PD_OK;
+}
+
+// ---- sampling head and generation loop ---------------------------------------
+
+namespace {
+
+struct HeadLayout {  // packed head: vocabulary matrix, its scales, the final LayerNorm gain
+    size_t w, s, gamma, total;
+};
+HeadLayout head_layout(const Shape& s, int V) {
+    HeadLayout p;
+    size_t o = 0;
+    p.w = o; o += align256((size_t)s.d * V);
+    p.s = o; o += align256((size_t)V * 4);
+    p.gamma = o; o += align256((size_t)s.d * 4);
+    p.total = o;
+    return p;
+}
+
+pd_status check_vocab(const Shape& s, int V, int B) {
+    if (V < 32 || V % 32 || V > (1 << 24)) return fail(PD_ERR_SHAPE, "vocab must be a positive multiple of 32");
+    if ((long long)s.d * V >= (1ll << 32)) return fail(PD_ERR_SHAPE, "the vocabulary matrix must be smaller than 4 GiB");
+    const int blk_ln = s.d / 128 < 1024 ? s.d / 128 : 1024;
+    int slots = 1;
+    const pd::SkqPlan pl = pd::qgemm_plan(B, s.d, V, auto_workgroups(B, s.d, V, 0, 1, blk_ln), 0, 1, blk_ln, &slots);
+    if ((long long)slots * pl.rows * V * 4 >= (1ll << 32)) return fail(PD_ERR_SHAPE, "batch x vocab too large");
+    return PD_OK;
+}
+
+struct HeadWs {  // scratch of the head for batch B
+    pd::SkqPlan pl;
+    size_t xres, hq, hs, part, nseg, total;
+};
+HeadWs head_ws(const Shape& s, int V, int B) {
+    HeadWs w;
+    const int blk_ln = s.d / 128 < 1024 ? s.d / 128 : 1024;
+    int slots = 1;
+    w.pl = pd::qgemm_plan(B, s.d, V, auto_workgroups(B, s.d, V, 0, 1, blk_ln), 0, 1, blk_ln, &slots);
+    size_t o = 0;
+    w.xres = o; o += align256((size_t)B * s.d * 4);
+    w.hq = o; o += align256((size_t)B * s.d * 3);
+    w.hs = o; o += align256((size_t)(s.d / 128) * 256 * 4);
+    w.part = o; o += align256((size_t)slots * w.pl.rows * V * 4);
+    w.nseg = o; o += align256(pd::skq_table_ints(w.pl.T, w.pl.G) * 4);
+    w.total = o;
+    return w;
+}
+
+// final LayerNorm + vocabulary projection of x [B][d] bf16 -> logits [B][V] fp32
+pd_status run_head(pd_handle* h, const unsigned char* packed_head, int V, const uint16_t* x, int B,
+                   float* logits, unsigned char* ws, hipStream_t st) {
+    const Shape& s = h->s;
+    const HeadLayout hl = head_layout(s, V);
+    HeadWs w = head_ws(s, V, B);
+    float* hs = reinterpret_cast<float*>(ws + w.hs);
+    float* part = reinterpret_cast<float*>(ws + w.part);
+    int* nseg = reinterpret_cast<int*>(ws + w.nseg);
+    w.pl.nseg = nseg;
+    PD_TRY_HIP(pd::launch_skq_table(w.pl, nseg, st), "segment table (head)");
+    PD_TRY_HIP(pd::launch_ln_first(x, reinterpret_cast<const float*>(packed_head + hl.gamma), B, s.d, h->desc.ln_eps,
+                                   reinterpret_cast<float*>(ws + w.xres), ws + w.hq, hs, 3, st), "final ln");
+    PD_TRY_HIP(pd::launch_qgemm(packed_head + hl.w, ws + w.hq, hs, part, B, s.d, V, w.pl, 3, st), "qgemm (vocab)");
+    PD_TRY_HIP(pd::launch_qgemm_reduce(part, reinterpret_cast<const float*>(packed_head + hl.s), logits, B, V, w.pl, st),
+               "logits");
+    return PD_OK;
+}
+
+struct GenWs {  // workspace of pd_generate: decode scratch, head scratch, logits, hidden state, step counter
+    size_t decode, head, logits, hidden, step, total;
+};
+GenWs gen_ws(const Shape& s, int V, int B, int L_ctx) {
+    GenWs g;
+    size_t o = 0;
+    g.decode = o; o += align256(workspace_layout(s, B, L_ctx).total);
+    g.head = o; o += align256(head_ws(s, V, B).total);
+    g.logits = o; o += align256((size_t)B * V * 4);
+    g.hidden = o; o += align256((size_t)B * s.d * 2);
+    g.step = o; o += 256;
+    g.total = o;
+    return g;
+}
+
+pd_status check_sampling(int V, int top_k, float top_p, float temperature) {
+    if (top_k < 1 || top_k > PD_MAX_TOP_K || top_k > V) return fail(PD_ERR_RANGE, "top_k must be in 1..64 and at most vocab");
+    if (!(top_p > 0.f) || top_p > 1.f) return fail(PD_ERR_RANGE, "top_p must be in (0, 1]");
+    if (!(temperature > 0.f)) return fail(PD_ERR_RANGE, "temperature must be positive");
+    return PD_OK;
+}
+
+}  // namespace
+
+pd_status pd_packed_head_bytes(const pd_model_desc* desc, int32_t vocab, size_t* bytes) {
+    Shape s;
+    pd_status rc = check_desc(desc, &s);
+    if (rc != PD_OK) return rc;
+    if ((rc = check_vocab(s, vocab, 1)) != PD_OK) return rc;
+    if (!bytes) return fail(PD_ERR_NULL, "bytes is NULL");
+    *bytes = head_layout(s, vocab).total;
+    return PD_OK;
+}
+
+pd_status pd_head_workspace_bytes(const pd_model_desc* desc, int32_t vocab, int32_t B, size_t* bytes) {
+    Shape s;
+    pd_status rc = check_desc(desc, &s);
+    if (rc != PD_OK) return rc;
+    if ((rc = check_batch(B, 32)) != PD_OK) return rc;
+    if ((rc = check_vocab(s, vocab, B)) != PD_OK) return rc;
+    if (!bytes) return fail(PD_ERR_NULL, "bytes is NULL");
+    *bytes = head_ws(s, vocab, B).total;
+    return PD_OK;
+}
+
+pd_status pd_generate_workspace_bytes(const pd_model_desc* desc, int32_t vocab, int32_t B, int32_t L_ctx,
+                                      size_t* bytes) {
+    Shape s;
+    pd_status rc = check_desc(desc, &s);
+    if (rc != PD_OK) return rc;
+    if ((rc = check_batch(B, L_ctx)) != PD_OK) return rc;
+    if ((rc = check_limits(s, B)) != PD_OK) return rc;
+    if ((rc = check_vocab(s, vocab, B)) != PD_OK) return rc;
+    if (!bytes) return fail(PD_ERR_NULL, "bytes is NULL");
+    *bytes = gen_ws(s, vocab, B, L_ctx).total;
+    return PD_OK;
+}
+
+pd_status pd_pack_head(pd_handle* h, const int8_t* w_vocab, const uint16_t* s_vocab, const uint16_t* gamma_f,
+                       int32_t vocab, void* packed_head, void* stream) {
+    if (!h) return fail(PD_ERR_NULL, "handle is NULL");
+    if (!w_vocab || !s_vocab || !gamma_f || !packed_head) return fail(PD_ERR_NULL, "NULL device pointer");
+    pd_status rc = check_vocab(h->s, vocab, 1);
+    if (rc != PD_OK) return rc;
+    if (!aligned(packed_head, 256)) return fail(PD_ERR_ALIGN, "packed_head must be 256-byte aligned");
+    const HeadLayout hl = head_layout(h->s, vocab);
+    unsigned char* dst = static_cast<unsigned char*>(packed_head);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    PD_TRY_HIP(pd::launch_pack_matrix(w_vocab, dst + hl.w, h->s.d, vocab, 0, 0, 0, st), "pack w_vocab");
+    PD_TRY_HIP(pd::launch_pack_vector(s_vocab, reinterpret_cast<float*>(dst + hl.s), vocab, 0, 0, 0, st), "pack s_vocab");
+    PD_TRY_HIP(pd::launch_pack_vector(gamma_f, reinterpret_cast<float*>(dst + hl.gamma), h->s.d, 0, 0, 0, st), "pack gamma_f");
+    return PD_OK;
+}
+
+pd_status pd_head_logits(pd_handle* h, const void* packed_head, int32_t vocab, const uint16_t* x, int32_t B,
+                         float* logits, void* workspace, size_t workspace_bytes, void* stream) {
+    if (!h) return fail(PD_ERR_NULL, "handle is NULL");
+    if (!packed_head || !x || !logits || !workspace) return fail(PD_ERR_NULL, "NULL device pointer");
+    pd_status rc = check_batch(B, 32);
+    if (rc != PD_OK) return rc;
+    if ((rc = check_limits(h->s, B)) != PD_OK) return rc;
+    if ((rc = check_vocab(h->s, vocab, B)) != PD_OK) return rc;
+    if (!aligned(packed_head, 256) || !aligned(workspace, 256) || !aligned(x, 16) || !aligned(logits, 16))
+        return fail(PD_ERR_ALIGN, "misaligned device pointer");
+    if (workspace_bytes < head_ws(h->s, vocab, B).total) return fail(PD_ERR_WORKSPACE, "workspace too small");
+    return run_head(h, static_cast<const unsigned char*>(packed_head), vocab, x, B, logits,
+                    static_cast<unsigned char*>(workspace), static_cast<hipStream_t>(stream));
+}
+
+pd_status pd_sample(const float* logits, int32_t B, int32_t vocab, int32_t top_k, float top_p, float temperature,
+                    const float* uniforms, int32_t* tokens, void* stream) {
+    if (!logits || !uniforms || !tokens) return fail(PD_ERR_NULL, "NULL device pointer");
+    if (B < 1 || B > 65535 || vocab < 1) return fail(PD_ERR_SHAPE, "B must be in 1..65535 and vocab positive");
+    pd_status rc = check_sampling(vocab, top_k, top_p, temperature);
+    if (rc != PD_OK) return rc;
+    PD_TRY_HIP(pd::launch_sample(logits, B, vocab, top_k, top_p, temperature, uniforms, nullptr, tokens,
+                                 static_cast<hipStream_t>(stream)), "sample");
+    return PD_OK;
+}
+
+pd_status pd_generate(pd_handle* h, const void* packed_weights, const void* packed_head, const uint16_t* embed,
+                      void* k_cache, void* v_cache, uint16_t* x, int32_t* positions, int32_t B, int32_t L_ctx,
+                      int32_t vocab, int32_t n_steps, int32_t top_k, float top_p, float temperature,
+                      const float* uniforms, int32_t* tokens_out, int32_t use_graph, void* workspace,
+                      size_t workspace_bytes, void* stream) {
+    if (!h) return fail(PD_ERR_NULL, "handle is NULL");
+    if (!packed_weights || !packed_head || !embed || !k_cache || !v_cache || !x || !positions || !uniforms ||
+        !tokens_out || !workspace)
+        return fail(PD_ERR_NULL, "NULL device pointer");
+    if (n_steps < 1 || n_steps > (1 << 20)) return fail(PD_ERR_RANGE, "n_steps must be in 1..2^20");
+    pd_status rc = check_sampling(vocab, top_k, top_p, temperature);
+    if (rc != PD_OK) return rc;
+    const Shape& s = h->s;
+    if ((rc = check_vocab(s, vocab, B > 0 ? B : 1)) != PD_OK) return rc;
+    const GenWs g = gen_ws(s, vocab, B > 0 && B <= 256 ? B : 1, L_ctx >= 32 && L_ctx % 32 == 0 ? L_ctx : 32);
+    unsigned char* ws = static_cast<unsigned char*>(workspace);
+    uint16_t* hidden = reinterpret_cast<uint16_t*>(ws + g.hidden);
+    rc = check_step_args(h, packed_weights, k_cache, v_cache, x, positions, B, L_ctx, hidden, workspace,
+                         workspace_bytes);
+    if (rc != PD_OK) return rc;
+    if (workspace_bytes < g.total) return fail(PD_ERR_WORKSPACE, "workspace too small");
+    if (!aligned(packed_head, 256) || !aligned(embed, 16)) return fail(PD_ERR_ALIGN, "misaligned device pointer");
+    if (use_graph && !stream) return fail(PD_ERR_STATE, "graph replay of the loop needs a non-null stream");
+    if (use_graph && h->profile_kernel) return fail(PD_ERR_STATE, "turn profile_kernel off before capturing");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    int32_t* step = reinterpret_cast<int32_t*>(ws + g.step);
+    float* logits = reinterpret_cast<float*>(ws + g.logits);
+
+    // one iteration: forward pass, logits, draw, feed the token back, advance positions
+    auto iteration = [&]() -> pd_status {
+        StepArgs a{static_cast<const unsigned char*>(packed_weights), k_cache, v_cache, x, positions, B, L_ctx,
+                   hidden, nullptr, 1, 0, s.L, ws + g.decode};
+        pd_status r = run_layers(h, a, st);
+        if (r != PD_OK) return r;
+        r = run_head(h, static_cast<const unsigned char*>(packed_head), vocab, hidden, B, logits, ws + g.head, st);
+        if (r != PD_OK) return r;
+        PD_TRY_HIP(pd::launch_sample(logits, B, vocab, top_k, top_p, temperature, uniforms, step, tokens_out, st), "sample");
+        PD_TRY_HIP(pd::launch_embed_advance(embed, s.d, vocab, tokens_out, B, x, positions, step, st), "embed");
+        return PD_OK;
+    };
+
+    PD_TRY_HIP(pd::launch_step_set(step, 0, st), "step counter");
+    if (!use_graph) {
+        for (int i = 0; i < n_steps; i++)
+            if ((rc = iteration()) != PD_OK) return rc;
+        return PD_OK;
+    }
+    if (h->gen_exec) { (void)hipGraphExecDestroy(h->gen_exec); h->gen_exec = nullptr; }
+    if (h->gen_graph) { (void)hipGraphDestroy(h->gen_graph); h->gen_graph = nullptr; }
+    PD_TRY_HIP(hipStreamBeginCapture(st, hipStreamCaptureModeThreadLocal), "begin capture");
+    rc = iteration();
+    hipGraph_t gr = nullptr;
+    hipError_t e = hipStreamEndCapture(st, &gr);
+    if (rc != PD_OK) { if (gr) (void)hipGraphDestroy(gr); return rc; }
+    if (e != hipSuccess) return fail_hip(e, "end capture");
+    h->gen_graph = gr;
+    e = hipGraphInstantiate(&h->gen_exec, gr, nullptr, nullptr, 0);
+    if (e != hipSuccess) return fail_hip(e, "graph instantiate");
+    for (int i = 0; i < n_steps; i++) PD_TRY_HIP(hipGraphLaunch(h->gen_exec, st), "graph launch");
     return PD_OK;
 }
 

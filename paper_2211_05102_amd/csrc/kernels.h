@@ -57,4 +57,13 @@ hipError_t launch_residual_ln(const float* part, SkqPlan pl, const float* scale,
                               int nd, hipStream_t stream);
 hipError_t launch_vec_absmax(const float* v, int n, float* out, hipStream_t stream);
 
+// ---- sampler.hip
+#define PD_MAX_TOP_K 64
+hipError_t launch_sample(const float* logits, int B, int V, int top_k, float top_p, float temperature,
+                         const float* uniforms, const int32_t* step, int32_t* tokens,
+                         hipStream_t stream);
+hipError_t launch_embed_advance(const uint16_t* embed, int d, int V, const int32_t* tokens, int B,
+                                uint16_t* x_next, int32_t* positions, int32_t* step, hipStream_t stream);
+hipError_t launch_step_set(int32_t* step, int value, hipStream_t stream);
+
 }  // namespace pd

@@ -78,3 +78,32 @@ def v_cache_to_library(v: torch.Tensor) -> torch.Tensor:
     # t = 16*kk + 8*i + 4*g + j ; c = 32*db + cl  ->  [tb][db][kk][g][cl][4*i + j]
     return (v.view(B, L // 32, 2, 2, 2, 4, dh // 32, 32)
             .permute(0, 1, 6, 2, 4, 7, 3, 5).contiguous().view(-1))
+
+
+class GenerateStack(DeviceStack):
+    """DeviceStack plus the sampling head, the embedding table, the uniforms and the
+    workspace of the generation loop."""
+
+    def __init__(self, workload, vocab: int, n_steps: int, **kw):
+        super().__init__(workload, **kw)
+        w = workload
+        self.vocab, self.n_steps = vocab, n_steps
+        self.head = synth.head_weights(w, vocab, self.device)
+        self.packed_head = torch.empty(binding.packed_head_bytes(self.desc, vocab), dtype=torch.uint8,
+                                       device=self.device)
+        self.dec.pack_head(self.head["w_vocab"], self.head["s_vocab"], self.head["gamma_f"], self.packed_head)
+        self.embed = self.head["embed"]
+        self.uniforms = synth.uniforms(n_steps, self.B, self.device)
+        self.tokens = torch.full((n_steps, self.B), -1, dtype=torch.int32, device=self.device)
+        self.gen_workspace = torch.empty(binding.generate_workspace_bytes(self.desc, vocab, self.B, w.l_ctx),
+                                         dtype=torch.uint8, device=self.device)
+        torch.cuda.synchronize()
+
+    def generate(self, top_k: int, top_p: float, temperature: float, use_graph: bool, stream=None,
+                 n_steps=None) -> torch.Tensor:
+        """Runs the loop in place on x_in / positions / caches; returns tokens [n_steps, B]."""
+        self.dec.generate(self.packed, self.packed_head, self.embed, self.k_cache, self.v_cache, self.x_in,
+                          self.positions, self.w.l_ctx, self.vocab, self.n_steps if n_steps is None else n_steps,
+                          top_k, top_p, temperature, self.uniforms, self.tokens, use_graph,
+                          self.gen_workspace, stream)
+        return self.tokens

@@ -20,7 +20,8 @@ import torch
 
 from .configs import MASTER_SEED, Workload
 
-_KINDS = ("w_in", "w_out", "gamma", "k_cache", "v_cache", "x", "positions")
+_KINDS = ("w_in", "w_out", "gamma", "k_cache", "v_cache", "x", "positions", "w_vocab", "gamma_f", "embed",
+          "uniforms")
 
 
 def _stream(device, layer: int, kind: str, seed: int = MASTER_SEED) -> torch.Generator:
@@ -103,3 +104,28 @@ def positions(w: Workload, device="cpu", batch: Optional[int] = None,
     g = _stream("cpu", 0, "positions", seed)
     p = torch.randint(w.pos_lo, w.pos_hi, (b,), generator=g, dtype=torch.int32)
     return p.to(device)
+
+
+def head_weights(w: Workload, vocab: int, device="cpu", sigma: float = 0.02,
+                 seed: int = MASTER_SEED) -> Dict[str, torch.Tensor]:
+    """Sampling head of the stack (stands in for PaLM's shared embedding matrix):
+
+    w_vocab [d_model, vocab] int8 + s_vocab [vocab] bf16 (same quantiser as the layers),
+    gamma_f [d_model] bf16 gain of the final LayerNorm, embed [vocab, d_model] bf16 ~ N(0, 1).
+    """
+    d = w.d_model
+    g = _stream(device, -1, "w_vocab", seed)
+    q, s = quantize_per_channel(torch.empty(d, vocab, dtype=torch.float32, device=device).normal_(0.0, sigma, generator=g))
+    g = _stream(device, -1, "gamma_f", seed)
+    gamma_f = (1.0 + torch.empty(d, dtype=torch.float32, device=device).normal_(0.0, 0.02, generator=g)
+               ).to(torch.bfloat16)
+    g = _stream(device, -1, "embed", seed)
+    embed = torch.empty(vocab, d, dtype=torch.float32, device=device).normal_(generator=g).to(torch.bfloat16)
+    return {"w_vocab": q, "s_vocab": s, "gamma_f": gamma_f, "embed": embed}
+
+
+def uniforms(n_steps: int, batch: int, device="cpu", seed: int = MASTER_SEED) -> torch.Tensor:
+    """The random numbers of the sampling loop, [n_steps, batch] fp32 in [0, 1): drawn here,
+    passed to both sides as input."""
+    g = _stream("cpu", -1, "uniforms", seed)
+    return torch.rand(n_steps, batch, generator=g, dtype=torch.float32).to(device)
