@@ -1,18 +1,27 @@
 """Benchmark of one decode step (the whole hot path over one batch of synthetic input).
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3_62b] [--no-graph]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3_62b]
 
-Prints ONE JSON line.  `value` is the achieved algorithmic HBM rate of the whole
-step (int8 weight bytes + KV bytes read, per second) with every input already
-resident in HBM; `ms_per_step` is the decode latency.  `roofline` covers the
-dominant kernel (the fused input projection), timed with HIP events on the
-stream it runs on, in a second pass of the same K steps so that the events do
-not perturb `value`.  `cpu_baseline` times the fp64 oracle on a bounded sample
-of the same workload on this machine's host cores.
+Prints ONE JSON line.
+  value / ms_per_step  wall clock over exactly K graph replays of the step of the headline
+                       workload, every input already resident in HBM; `value` is the achieved
+                       algorithmic HBM rate (int8 weight bytes + KV bytes read, per second)
+  timing               per-step HIP events on the launch stream: median and min, graph replay
+                       and eager launches
+  roofline             the dominant kernel (fused input projection), HIP events around every
+                       launch of a second, eager pass of the same K steps
+  kernels              the same event timing for the other kernel classes
+  per_config           every named workload: ms/step (median, min), tokens/s, algorithmic GB/s,
+                       fraction of the HBM peak, int8 matrix-pipe utilisation, two-phase bound
+  generate             the generation loop (64 steps, sampling head included): ms per token
+  copy_ceiling         a plain device-to-device copy, the practical bandwidth ceiling
+  cpu_baseline         the fp64 oracle on a bounded sample of the headline workload
 """
 import argparse
 import json
 import os
+import re
+import statistics
 import sys
 import time
 
@@ -20,7 +29,10 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, published
+HBM_PEAK_GBPS = 8000.0     # MI355X HBM3E, published
+INT8_PEAK_OPS = 5.0e15     # dense int8 MFMA, published
+BF16_PEAK_FLOPS = 2.5e15   # dense bf16 MFMA, published
+ACT_PLANES = 3             # int8 digit planes per activation (the library's default)
 
 
 def cpu_baseline(w, stack_rows=4, seconds_budget=20.0):
@@ -63,20 +75,59 @@ def cpu_baseline(w, stack_rows=4, seconds_budget=20.0):
     }
 
 
-# HBM bytes one launch of the input projection moves, from the rocprofv3 FETCH_SIZE / WRITE_SIZE passes
-# summarised in profiles/hbm_traffic_pmc_c3_62b_layer.txt (counters scaled by a plain 1 GiB copy):
-# (306898.5 * 2.0 + 29696.0 * 1.0) KiB.  Other workloads: not measured.
-TRAFFIC_BYTES_PER_LAUNCH = {"c3_62b": int((306898.5 * 2.0 + 29696.0) * 1024)}
+def traffic_from_profile(workload_name):
+    """HBM bytes one launch of the input projection moves, from the committed rocprofv3 counter
+    summary (a line `input_projection_hbm_bytes_per_launch: N`); None when there is no such file."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_pmc_{workload_name}_layer.txt")
+    try:
+        m = re.search(r"^input_projection_hbm_bytes_per_launch:\s*(\d+)", open(path).read(), re.M)
+        return int(m.group(1)) if m else None
+    except OSError:
+        return None
 
 
-def time_workload(w, steps, warmup):
-    """Graph-replay time of one decode step of workload `w` (all inputs resident)."""
+def event_times(run_once, n, stream):
+    """Milliseconds of each of n calls of run_once(), from events recorded on `stream`."""
     import torch
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(n + 1)]
+    ev[0].record(stream)
+    for i in range(n):
+        run_once()
+        ev[i + 1].record(stream)
+    torch.cuda.synchronize()
+    return [ev[i].elapsed_time(ev[i + 1]) for i in range(n)]
+
+
+def summarize(w, positions, ms):
     from workloads import configs as C
-    from paper_2211_05102_amd import harness
-    st = harness.DeviceStack(w)
-    positions = st.positions.cpu().tolist()
     bytes_step = C.algorithmic_bytes(w, positions)
+    wbytes = C.weight_bytes(w)
+    kvbytes = C.kv_read_bytes(w, positions)
+    s = ms * 1e-3
+    int8_ops = 2.0 * wbytes * w.batch * ACT_PLANES
+    return {
+        "ms_per_step": ms,
+        "tokens_per_s": w.batch / s,
+        "GB/s": bytes_step / s / 1e9,
+        "hbm_peak_frac": bytes_step / s / 1e9 / HBM_PEAK_GBPS,
+        "int8_mfma_util": int8_ops / s / INT8_PEAK_OPS,
+        # lower bounds of the step: bytes at the HBM peak; projections on the matrix pipe (as this
+        # library computes them: 3 int8 planes; and as one bf16 pass) followed by the KV stream
+        "bound_ms": {"hbm": bytes_step / (HBM_PEAK_GBPS * 1e9) * 1e3,
+                     "two_phase_int8x3": (int8_ops / INT8_PEAK_OPS + kvbytes / (HBM_PEAK_GBPS * 1e9)) * 1e3,
+                     "two_phase_bf16": (2.0 * wbytes * w.batch / BF16_PEAK_FLOPS + kvbytes / (HBM_PEAK_GBPS * 1e9)) * 1e3},
+    }
+
+
+def time_workload(w, steps, warmup, eager_steps=0):
+    """Per-step event timing of workload `w`: graph replay (and eager launches)."""
+    import torch
+    from paper_2211_05102_amd import harness
+    t0 = time.perf_counter()
+    st = harness.DeviceStack(w)
+    torch.cuda.synchronize()
+    setup = time.perf_counter() - t0
+    positions = st.positions.cpu().tolist()
     stream = torch.cuda.Stream()
     with torch.cuda.stream(stream):
         st.dec.graph_capture(st.packed, st.k_cache, st.v_cache, st.x_in, st.positions, w.l_ctx,
@@ -84,18 +135,61 @@ def time_workload(w, steps, warmup):
         for _ in range(warmup):
             st.dec.graph_replay(stream)
         torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(steps):
-            st.dec.graph_replay(stream)
-        torch.cuda.synchronize()
-        dt = (time.perf_counter() - t0) / steps
+        t_graph = event_times(lambda: st.dec.graph_replay(stream), steps, stream)
+        t_eager = event_times(lambda: st.step(stream), eager_steps, stream) if eager_steps else []
         st.dec.check_async(st.workspace, stream)
     st.dec.graph_release()
     del st
     torch.cuda.empty_cache()
-    gbps = bytes_step / dt / 1e9
-    return {"ms_per_step": dt * 1e3, "GB/s": gbps, "hbm_peak_frac": gbps / HBM_PEAK_GBPS,
-            "tokens_per_s": w.batch / dt}
+    out = summarize(w, positions, statistics.median(t_graph))
+    out.update({"ms_min": min(t_graph), "steps": steps, "launch": "hipGraph replay", "setup_s": round(setup, 1)})
+    if t_eager:
+        out["eager_ms_median"] = statistics.median(t_eager)
+        out["eager_ms_min"] = min(t_eager)
+    return out
+
+
+def time_generate(w, n_steps, vocab, top_k, top_p, temperature):
+    """The generation loop on workload `w` (positions chosen so that the last generated token fills
+    the cache): milliseconds per token, graph replay of one step per token."""
+    import torch
+    from paper_2211_05102_amd import harness
+    start = w.l_ctx - n_steps
+    wg = w.with_(positions="ragged", pos_lo=start, pos_hi=start + 1, name=f"{w.name}[generate]")
+    st = harness.GenerateStack(wg, vocab, n_steps)
+    stream = torch.cuda.Stream()
+    out = {}
+    with torch.cuda.stream(stream):
+        for use_graph in (True, False):
+            st.positions.fill_(start)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            st.generate(top_k, top_p, temperature, use_graph, stream)
+            torch.cuda.synchronize()
+            dt = time.perf_counter() - t0
+            st.dec.check_async(st.gen_workspace, stream)
+            out["graph" if use_graph else "eager"] = dt * 1e3 / n_steps
+    tok = st.tokens.cpu()
+    del st
+    torch.cuda.empty_cache()
+    return {"n_steps": n_steps, "vocab": vocab, "top_k": top_k, "top_p": top_p, "temperature": temperature,
+            "kv_len_start": start, "ms_per_token_graph": out["graph"], "ms_per_token_eager": out["eager"],
+            "tokens_per_s": wg.batch / (out["graph"] * 1e-3),
+            "distinct_tokens_drawn": int(tok.unique().numel())}
+
+
+def copy_ceiling():
+    import torch
+    n = 1 << 32
+    src = torch.empty(n, dtype=torch.uint8, device="cuda").fill_(3)
+    dst = torch.empty_like(src)
+    stream = torch.cuda.current_stream()
+    dst.copy_(src)
+    ms = event_times(lambda: dst.copy_(src), 5, stream)
+    del src, dst
+    torch.cuda.empty_cache()
+    return {"GB/s_read_plus_write": 2 * n / (min(ms) * 1e-3) / 1e9, "bytes_copied": n,
+            "what": "torch device-to-device copy of 4 GiB, best of 5"}
 
 
 def main():
@@ -106,15 +200,12 @@ def main():
     ap.add_argument("--workload", default="c3_62b")
     ap.add_argument("--layers", type=int, default=0,
                     help="run a shorter stack of the same layer shape (kernel tuning; not the headline workload)")
-    ap.add_argument("--no-graph", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--headline-only", action="store_true",
+                    help="skip per_config, generate and copy_ceiling (profiling runs)")
     ap.add_argument("--gemm-wg-in", type=int, default=0)
     ap.add_argument("--gemm-wg-out", type=int, default=0)
     ap.add_argument("--attn-bps", type=int, default=0)
-    ap.add_argument("--act-digits", type=int, default=0)
-    ap.add_argument("--all-configs", action="store_true",
-                    help="also time the other named workloads (graph replay, 5 steps each) and add them to the "
-                         "JSON line as per_config; the headline value stays the --workload one")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three plain 1 GiB device copies (reference for scaling rocprofv3's "
                          "FETCH_SIZE / WRITE_SIZE counters in the --pmc passes)")
@@ -135,7 +226,7 @@ def main():
     t_setup = time.perf_counter()
     st = harness.DeviceStack(w)
     for name, val in (("gemm_workgroups_in", args.gemm_wg_in), ("gemm_workgroups_out", args.gemm_wg_out),
-                      ("attn_blocks_per_split", args.attn_bps), ("act_digits", args.act_digits)):
+                      ("attn_blocks_per_split", args.attn_bps)):
         if val:
             st.dec.set_option(name, val)
     torch.cuda.synchronize()
@@ -152,27 +243,21 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-    use_graph = not args.no_graph
     with torch.cuda.stream(stream):
-        if use_graph:
-            st.dec.graph_capture(st.packed, st.k_cache, st.v_cache, st.x_in, st.positions, w.l_ctx,
-                                 st.x_out, st.workspace, stream)
-
-        def one_step():
-            if use_graph:
-                st.dec.graph_replay(stream)
-            else:
-                st.step(stream)
-
+        st.dec.graph_capture(st.packed, st.k_cache, st.v_cache, st.x_in, st.positions, w.l_ctx,
+                             st.x_out, st.workspace, stream)
         for _ in range(args.warmup):
-            one_step()
+            st.dec.graph_replay(stream)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for _ in range(args.steps):
-            one_step()
+            st.dec.graph_replay(stream)
         torch.cuda.synchronize()
         elapsed = time.perf_counter() - t0
         st.dec.check_async(st.workspace, stream)
+        # per-step events: graph replay, then eager launches
+        t_graph = event_times(lambda: st.dec.graph_replay(stream), args.steps, stream)
+        t_eager = event_times(lambda: st.step(stream), max(3, args.steps // 2), stream)
 
         # second pass: the same K steps, eager launches, events around the dominant kernel
         st.dec.set_option("profile_kernel", 1)
@@ -189,6 +274,7 @@ def main():
             ms, n = st.dec.profile_read()
             per_kernel[kname] = {"avg_us": 1e3 * ms / max(n, 1), "launches": n}
         st.dec.set_option("profile_kernel", 0)
+    st.dec.graph_release()
 
     ms_per_step = elapsed * 1e3 / args.steps
     gbps = bytes_step / (elapsed / args.steps) / 1e9
@@ -196,6 +282,7 @@ def main():
     k_bytes = w.d_model * w.n_in  # int8 weight bytes the input projection streams per launch
     k_gbps = k_bytes / k_avg_s / 1e9
     per_kernel["qgemm_in"] = {"avg_us": k_avg_s * 1e6, "launches": k_launches}
+    headline = summarize(w, positions, ms_per_step)
 
     out = {
         "metric": "decode_achieved_hbm_bandwidth_int8_mqa",
@@ -212,26 +299,37 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "int8",  # int8 x int8 -> int32 MFMA on block fixed-point activations; fp32 folds and softmax
+        # int8 weights x three int8 digit planes of block fixed-point activations (23 bits + sign per
+        # 128-element block) on the int8 MFMA with exact int32 sums; fp32 folds, softmax, LayerNorm
+        "dtype": "int8 weights x 3-plane int8 block-fixed-point activations, int32 sums, fp32 elsewhere",
         "data": "synthetic",
         "config": {"workload": w.name, "n_layers": w.n_layers, "d_model": w.d_model,
                    "n_heads": w.n_heads, "d_head": w.d_head, "d_ff": w.d_ff, "batch": w.batch,
                    "kv_len": w.l_ctx, "positions": w.positions, "weights": "int8 per-channel",
-                   "launch": "hipGraph replay" if use_graph else "eager", "setup_s": round(t_setup, 1)},
+                   "launch": "hipGraph replay", "setup_s": round(t_setup, 1)},
+        "timing": {"graph_ms_median": statistics.median(t_graph), "graph_ms_min": min(t_graph),
+                   "eager_ms_median": statistics.median(t_eager), "eager_ms_min": min(t_eager),
+                   "clock": "HIP events on the launch stream, one pair per step"},
+        "int8_mfma_util": headline["int8_mfma_util"],
+        "bound_ms": headline["bound_ms"],
         "roofline": {"bound": "hbm", "kernel": "qgemm_kernel (fused input projection)",
                      "achieved": k_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": k_gbps / HBM_PEAK_GBPS, "traffic": TRAFFIC_BYTES_PER_LAUNCH.get(args.workload),
+                     "frac": k_gbps / HBM_PEAK_GBPS, "traffic": traffic_from_profile(args.workload),
                      "bytes_per_launch": k_bytes, "avg_launch_us": k_avg_s * 1e6},
         "kernels": per_kernel,
     }
     del st
     torch.cuda.empty_cache()
-    if args.all_configs:
-        out["per_config"] = {w.name: {"ms_per_step": ms_per_step, "GB/s": gbps, "hbm_peak_frac": gbps / HBM_PEAK_GBPS}}
-        for name in ("c1_tiny", "c2_8b", "c4_540b_shard8", "c5_62b_long"):
-            if name == args.workload:
-                continue
-            out["per_config"][name] = time_workload(WORKLOADS[name], steps=5, warmup=2)
+    if not args.headline_only:
+        out["copy_ceiling"] = copy_ceiling()
+        out["generate"] = time_generate(w, 64, 256000, 40, 0.9, 1.0)
+        mine = summarize(w, positions, statistics.median(t_graph))
+        mine.update({"ms_min": min(t_graph), "steps": args.steps, "launch": "hipGraph replay",
+                     "eager_ms_median": statistics.median(t_eager), "eager_ms_min": min(t_eager)})
+        out["per_config"] = {w.name: mine}
+        for name, k, e in (("c1_tiny", 50, 20), ("c2_8b", 30, 10), ("c4_540b_shard8", 10, 4), ("c5_62b_long", 6, 0)):
+            if name != args.workload:
+                out["per_config"][name] = time_workload(WORKLOADS[name], steps=k, warmup=2, eager_steps=e)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(out))
