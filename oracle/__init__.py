@@ -203,11 +203,13 @@ def decode_layer(desc: _Desc, weights: dict, kc: np.ndarray, vc: np.ndarray,
     pos = np.ascontiguousarray(positions, dtype=np.int32)
     rows = np.arange(R, dtype=np.int32) if cache_row is None else np.ascontiguousarray(cache_row, dtype=np.int32)
     assert pos.shape == (R,) and rows.shape == (R,)
-    assert kc.shape[1:] == (l_ctx, desc.d_head) and vc.shape == kc.shape
+    G = desc.n_kv_heads
+    tail = (l_ctx, desc.d_head) if G == 1 else (G, l_ctx, desc.d_head)
+    assert kc.shape[1:] == tail and vc.shape == kc.shape, (kc.shape, tail)
     assert rows.max() < kc.shape[0]
     w_in, w_out = _i8(weights["w_in"]), _i8(weights["w_out"])
     s_in, s_out, gamma = _bits(weights["s_in"]), _bits(weights["s_out"]), _bits(weights["gamma"])
-    n_in = desc.n_heads * desc.d_head + 2 * desc.d_head + 2 * desc.d_ff
+    n_in = desc.n_heads * desc.d_head + 2 * G * desc.d_head + 2 * desc.d_ff
     k_out = desc.n_heads * desc.d_head + desc.d_ff
     assert w_in.shape == (desc.d_model, n_in) and w_out.shape == (k_out, desc.d_model)
     rc = lib().orc_decode_layer(ctypes.byref(desc), _p(w_in, np.int8), _p(s_in, np.uint16),

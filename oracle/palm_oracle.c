@@ -222,9 +222,9 @@ void orc_swiglu(const double* g, const double* u, int32_t F, double* a) {
  * w_in  [d][n_in] int8, columns q(H*dh) | k(dh) | v(dh) | gate(F) | up(F)
  * s_in  [n_in] bf16 bits;  w_out [H*dh + F][d] int8, rows attn | ffn;  s_out [d]
  * gamma [d] bf16 bits
- * kc, vc: this layer's cache, [rows][L_ctx][dh] bf16 bits; row r uses cache
- *         row cache_row[r]; slot positions[r] is WRITTEN, slots 0..positions[r]
- *         are read, nothing else is touched.
+ * kc, vc: this layer's cache, [rows][n_kv_heads][L_ctx][dh] bf16 bits; row r uses
+ *         cache row cache_row[r]; slot positions[r] of every K/V head is WRITTEN,
+ *         slots 0..positions[r] are read, nothing else is touched.
  * x:   [R][d] fp64, in/out.  add_residual = 0 stores only the block's
  *      contribution (a shard's unreduced partial) instead of x + contribution.
  * Returns 0, or -1 on a bad argument.
@@ -235,10 +235,14 @@ int orc_decode_layer(const orc_desc* m, const int8_t* w_in, const uint16_t* s_in
                      const int32_t* positions, int32_t R, int32_t L_ctx,
                      double* x, int32_t add_residual) {
     int32_t d = m->d_model, H = m->n_heads, dh = m->d_head, F = m->d_ff;
-    if (m->n_kv_heads != 1 || R < 1 || L_ctx < 1 || (dh & 1)) return -1;
+    /* K/V heads: 1 = multiquery (Section 3.3), H = multihead (every query head has its
+     * own K/V head).  With G heads the columns of w_in are q(H*dh) | k(G*dh) | v(G*dh) |
+     * gate | up and a cache row is [G][L_ctx][dh]. */
+    int32_t G = m->n_kv_heads;
+    if ((G != 1 && G != H) || R < 1 || L_ctx < 1 || (dh & 1)) return -1;
     for (int32_t r = 0; r < R; r++)
         if (positions[r] < 0 || positions[r] >= L_ctx) return -1;
-    int32_t n_in = H * dh + 2 * dh + 2 * F, k_out = H * dh + F;
+    int32_t n_in = H * dh + 2 * G * dh + 2 * F, k_out = H * dh + F;
 
     double* h = (double*)malloc((size_t)R * d * sizeof(double));
     double* z = (double*)malloc((size_t)R * n_in * sizeof(double));
@@ -255,20 +259,24 @@ int orc_decode_layer(const orc_desc* m, const int8_t* w_in, const uint16_t* s_in
         double* zr = z + (size_t)r * n_in;
         double* q = zr;
         double* k = zr + (size_t)H * dh;
-        double* v = k + dh;
-        double* g = v + dh;
+        double* v = k + (size_t)G * dh;
+        double* g = v + (size_t)G * dh;
         double* u = g + F;
         int32_t p = positions[r];
         for (int32_t j = 0; j < H; j++) orc_rope(q + (size_t)j * dh, dh, p, m->rope_base);
-        orc_rope(k, dh, p, m->rope_base);
-        uint16_t* Kr = kc + (size_t)cache_row[r] * L_ctx * dh;
-        uint16_t* Vr = vc + (size_t)cache_row[r] * L_ctx * dh;
-        for (int32_t c = 0; c < dh; c++) {
-            Kr[(size_t)p * dh + c] = orc_f64_to_bf16(k[c]);
-            Vr[(size_t)p * dh + c] = orc_f64_to_bf16(v[c]);
-        }
         double* oar = oa + (size_t)r * k_out;
-        orc_attend_mqa(q, Kr, Vr, H, dh, p + 1, oar, NULL);
+        for (int32_t j = 0; j < G; j++) {
+            orc_rope(k + (size_t)j * dh, dh, p, m->rope_base);
+            uint16_t* Kr = kc + ((size_t)cache_row[r] * G + j) * L_ctx * dh;
+            uint16_t* Vr = vc + ((size_t)cache_row[r] * G + j) * L_ctx * dh;
+            for (int32_t c = 0; c < dh; c++) {
+                Kr[(size_t)p * dh + c] = orc_f64_to_bf16(k[(size_t)j * dh + c]);
+                Vr[(size_t)p * dh + c] = orc_f64_to_bf16(v[(size_t)j * dh + c]);
+            }
+            /* the query heads that share K/V head j: all H of them (multiquery) or head j alone */
+            int32_t per = H / G;
+            orc_attend_mqa(q + (size_t)j * per * dh, Kr, Vr, per, dh, p + 1, oar + (size_t)j * per * dh, NULL);
+        }
         orc_swiglu(g, u, F, oar + (size_t)H * dh);
     }
 

@@ -551,3 +551,69 @@ def test_head_logits_are_layernorm_then_projection():
     h = g64 * (x - mu) / np.sqrt(((x - mu) ** 2).mean(axis=1, keepdims=True) + 1e-6)
     want = (h @ w.double().numpy()) * s64
     assert np.max(np.abs(got - want)) <= 1e-12 * np.max(np.abs(want))
+
+
+# ------------------------------------------ multihead variant (Section 3.3, 4.2) ---
+
+def _mha_inputs(seed=21):
+    rng = np.random.default_rng(seed)
+    H, dh, d, F, L, R = 3, 8, 32, 16, 12, 2
+    mq = Workload("mq", 1, d, H, dh, F, R, L)
+    mh = mq.with_(n_kv_heads=H)
+    w_mq = synth.layer_weights(mq, 0, "cpu")
+    # multihead weights whose K and V columns are the multiquery ones copied to every head
+    q_cols = w_mq["w_in"][:, :H * dh]
+    k_cols = w_mq["w_in"][:, H * dh:H * dh + dh]
+    v_cols = w_mq["w_in"][:, H * dh + dh:H * dh + 2 * dh]
+    ffn = w_mq["w_in"][:, H * dh + 2 * dh:]
+    s = w_mq["s_in"]
+    w_mh = dict(w_mq)
+    w_mh["w_in"] = torch.cat([q_cols] + [k_cols] * H + [v_cols] * H + [ffn], dim=1).contiguous()
+    w_mh["s_in"] = torch.cat([s[:H * dh]] + [s[H * dh:H * dh + dh]] * H + [s[H * dh + dh:H * dh + 2 * dh]] * H
+                             + [s[H * dh + 2 * dh:]]).contiguous()
+    kc = rng.integers(0x3c00, 0x4000, (R, L, dh)).astype(np.uint16)
+    vc = rng.integers(0xbc00, 0xc000, (R, L, dh)).astype(np.uint16)
+    x = rng.standard_normal((R, d))
+    pos = np.array([5, 11], dtype=np.int32)
+    return mq, mh, w_mq, w_mh, kc, vc, x, pos, H
+
+
+def test_multihead_layer_with_replicated_kv_equals_multiquery_layer():
+    mq, mh, w_mq, w_mh, kc, vc, x, pos, H = _mha_inputs()
+    x1, k1, v1 = x.copy(), kc.copy(), vc.copy()
+    oracle.decode_layer(oracle.make_desc(mq), w_mq, k1, v1, pos, x1, mq.l_ctx)
+    x2 = x.copy()
+    k2 = np.repeat(kc[:, None], H, axis=1).copy()  # [R, H, L, dh]: every head a copy of the shared one
+    v2 = np.repeat(vc[:, None], H, axis=1).copy()
+    oracle.decode_layer(oracle.make_desc(mh), w_mh, k2, v2, pos, x2, mh.l_ctx)
+    assert np.max(np.abs(x1 - x2)) <= 1e-12 * np.max(np.abs(x1))
+    for j in range(H):
+        assert np.array_equal(k2[:, j], k1) and np.array_equal(v2[:, j], v1)  # same appended slot in every head
+
+
+def test_multihead_heads_read_their_own_cache_only():
+    _, mh, _, w_mh, kc, vc, x, pos, H = _mha_inputs(22)
+    desc = oracle.make_desc(mh)
+    # zero output rows for everything but the attention output of head 1: x' - x shows head 1 alone
+    wts = dict(w_mh)
+    w_out = torch.zeros_like(wts["w_out"])
+    dh = mh.d_head
+    w_out[dh:2 * dh] = wts["w_out"][dh:2 * dh]
+    wts["w_out"] = w_out
+    k2 = np.repeat(kc[:, None], H, axis=1).copy()
+    v2 = np.repeat(vc[:, None], H, axis=1).copy()
+    base = x.copy()
+    oracle.decode_layer(desc, wts, k2.copy(), v2.copy(), pos, base, mh.l_ctx)
+    for head, changes in ((0, False), (1, True), (2, False)):
+        kk, vv = k2.copy(), v2.copy()
+        vv[:, head, 2] ^= 0x0100  # perturb one cached value row of that head (a live slot for both rows)
+        out = x.copy()
+        oracle.decode_layer(desc, wts, kk, vv, pos, out, mh.l_ctx)
+        assert (np.max(np.abs(out - base)) > 0) == changes, head
+
+
+def test_multihead_byte_model_scales_kv_by_heads():
+    from workloads import configs as C
+    w = Workload("t", 4, 256, 8, 64, 512, 2, 128)
+    assert C.kv_read_bytes(w.with_(n_kv_heads=8), [127, 63]) == 8 * C.kv_read_bytes(w, [127, 63])
+    assert w.with_(n_kv_heads=8).n_in == w.n_in + 2 * 7 * 64

@@ -38,8 +38,9 @@ class Workload:
 
     @property
     def n_in(self) -> int:
-        """Columns of the fused input projection: q | k | v | gate | up."""
-        return self.n_heads * self.d_head + 2 * self.d_head + 2 * self.d_ff
+        """Columns of the fused input projection: q | k | v | gate | up (k and v have one
+        block of d_head columns per K/V head)."""
+        return self.n_heads * self.d_head + 2 * self.n_kv_heads * self.d_head + 2 * self.d_ff
 
     @property
     def k_out(self) -> int:

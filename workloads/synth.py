@@ -84,13 +84,15 @@ def hidden_state(w: Workload, device="cpu", batch: Optional[int] = None,
 
 def kv_layer(w: Workload, layer: int, device="cpu", batch: Optional[int] = None,
              seed: int = MASTER_SEED):
-    """Cached K and V of one layer, canonical [B, L_ctx, d_head] bf16 ~ N(0, 1).
+    """Cached K and V of one layer, canonical [B, L_ctx, d_head] bf16 ~ N(0, 1)
+    ([B, n_kv_heads, L_ctx, d_head] for a multihead workload).
     K is taken to be already rotated (the cache stores post-RoPE keys)."""
     b = w.batch if batch is None else batch
+    shape = (b, w.l_ctx, w.d_head) if w.n_kv_heads == 1 else (b, w.n_kv_heads, w.l_ctx, w.d_head)
     out = []
     for kind in ("k_cache", "v_cache"):
         g = _stream(device, layer, kind, seed)
-        t = torch.empty(b, w.l_ctx, w.d_head, dtype=torch.float32, device=device).normal_(generator=g)
+        t = torch.empty(*shape, dtype=torch.float32, device=device).normal_(generator=g)
         out.append(t.to(torch.bfloat16))
     return out[0], out[1]
 
