@@ -29,16 +29,20 @@
  *   w_out  [k_out][d_model] int8 row-major, rows attention-out(H*dh) | FFN activation(F)
  *   s_out  [d_model]        bf16
  *   gamma  [d_model]        bf16 LayerNorm gain (no bias; eps inside the root)
- *   K, V   [B][L_ctx][d_head] bf16 per layer (K holds rotated keys)
- *   with n_in = H*dh + 2*dh + 2*F and k_out = H*dh + F.
+ *   K, V   [B][G][L_ctx][d_head] bf16 per layer (K holds rotated keys), G = n_kv_heads
+ *   with n_in = H*dh + 2*G*dh + 2*F (k and v: one block of dh columns per K/V head)
+ *   and k_out = H*dh + F.  G = 1 is the multiquery layout of Section 3.3 (all query
+ *   heads share one K/V head); G = H is the multihead baseline it is compared with
+ *   (Section 3.3, Section 4.2); any G that divides H works (query heads j*H/G ..
+ *   (j+1)*H/G - 1 read K/V head j).
  *
  * Library-side layouts (Section 3.5 lists in-memory tensor layout among the
  * low-level optimisations; these are this library's, chosen so that every
  * 64-lane wavefront streams 1 KiB contiguous pieces straight into MFMA operands)
  *   packed layer  = pd_packed_layer_bytes() bytes made by pd_pack_layer().
- *   K cache [n_layers][B][L_ctx/32][dh/16][2][32][8] bf16:
+ *   K cache [n_layers][B*G][L_ctx/32][dh/16][2][32][8] bf16 (K/V head j of row b at b*G + j):
  *       element (l,b,t,c) -> [l][b][t/32][c/16][(c%16)/8][t%32][c%8]
- *   V cache [n_layers][B][L_ctx/32][dh/32][2][2][32][8] bf16:
+ *   V cache [n_layers][B*G][L_ctx/32][dh/32][2][2][32][8] bf16:
  *       element (l,b,t,c) -> [l][b][t/32][c/32][(t%32)/16][(t%8)/4][c%32][4*((t%16)/8) + t%4]
  *   L_ctx must be a multiple of 32.  pd_kv_import()/pd_kv_export() convert one
  *   layer between canonical and library layout.
@@ -68,7 +72,8 @@ enum {
 
 /* Model description (Section 2.2 notation: d_model = E, d_ff = F, n_heads = H).
  * Supported: d_model % 128 == 0, d_ff % 128 == 0, (H*d_head) % 128 == 0,
- * d_head in {64, 128, 256}, 1 <= n_heads <= 32, n_kv_heads == 1; each projection
+ * d_head in {64, 128, 256}, 1 <= n_heads <= 256, n_kv_heads divides n_heads and at
+ * most 32 query heads share a K/V head; each projection
  * matrix smaller than 4 GiB; batch 1..256; L_ctx a multiple of 32.  Anything else
  * is refused with PD_ERR_SHAPE by every call that takes the description. */
 typedef struct pd_model_desc {
@@ -77,7 +82,7 @@ typedef struct pd_model_desc {
     int32_t n_heads;
     int32_t d_head;
     int32_t d_ff;       /* per SwiGLU branch */
-    int32_t n_kv_heads; /* must be 1 (multiquery, Section 3.3) */
+    int32_t n_kv_heads; /* 1 = multiquery (Section 3.3), n_heads = multihead */
     float rope_base;    /* 10000 */
     float ln_eps;       /* 1e-6 */
     int32_t flags;      /* reserved, 0 */

@@ -201,14 +201,14 @@ class Decoder:
                                    _stream(stream)))
 
     def kv_import(self, canonical: torch.Tensor, cache: torch.Tensor, layer: int, is_v: bool, stream=None) -> None:
-        B, L_ctx, _ = canonical.shape
+        B, L_ctx = canonical.shape[0], canonical.shape[-2]  # [B, L, dh] or [B, G, L, dh]
         assert canonical.dtype == torch.bfloat16 and canonical.is_contiguous()
         _check(lib().pd_kv_import(self._h, _ptr(canonical), _ptr(cache), ctypes.c_int32(layer),
                                   ctypes.c_int32(B), ctypes.c_int32(L_ctx), ctypes.c_int32(int(is_v)),
                                   _stream(stream)))
 
     def kv_export(self, cache: torch.Tensor, canonical: torch.Tensor, layer: int, is_v: bool, stream=None) -> None:
-        B, L_ctx, _ = canonical.shape
+        B, L_ctx = canonical.shape[0], canonical.shape[-2]  # [B, L, dh] or [B, G, L, dh]
         assert canonical.dtype == torch.bfloat16 and canonical.is_contiguous()
         _check(lib().pd_kv_export(self._h, _ptr(cache), _ptr(canonical), ctypes.c_int32(layer),
                                   ctypes.c_int32(B), ctypes.c_int32(L_ctx), ctypes.c_int32(int(is_v)),

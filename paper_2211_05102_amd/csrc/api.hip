@@ -36,27 +36,28 @@ inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
 struct Shape {
-    int L, d, H, dh, F, n_qkv, n_in, k_out;
+    int L, d, H, G, dh, F, n_qkv, n_in, k_out;  // G = K/V heads
 };
 
 pd_status check_desc(const pd_model_desc* m, Shape* s) {
     if (!m) return fail(PD_ERR_NULL, "desc is NULL");
     if (m->n_layers < 1 || m->d_model < 128 || m->d_model % 128) return fail(PD_ERR_SHAPE, "d_model must be a positive multiple of 128, n_layers >= 1");
     if (m->d_head != 64 && m->d_head != 128 && m->d_head != 256) return fail(PD_ERR_SHAPE, "d_head must be 64, 128 or 256");
-    if (m->n_heads < 1 || m->n_heads > 32) return fail(PD_ERR_SHAPE, "n_heads must be in 1..32");
-    if (m->n_kv_heads != 1) return fail(PD_ERR_SHAPE, "n_kv_heads must be 1 (multiquery)");
+    if (m->n_heads < 1 || m->n_heads > 256) return fail(PD_ERR_SHAPE, "n_heads must be in 1..256");
+    if (m->n_kv_heads < 1 || m->n_heads % m->n_kv_heads) return fail(PD_ERR_SHAPE, "n_kv_heads must divide n_heads");
+    if (m->n_heads / m->n_kv_heads > 32) return fail(PD_ERR_SHAPE, "at most 32 query heads may share one K/V head");
     if (m->d_ff < 128 || m->d_ff % 128) return fail(PD_ERR_SHAPE, "d_ff must be a positive multiple of 128");
     long long k_out = (long long)m->n_heads * m->d_head + m->d_ff;
     if ((m->n_heads * m->d_head) % 128) return fail(PD_ERR_SHAPE, "n_heads*d_head must be a multiple of 128");
-    long long n_in = (long long)m->n_heads * m->d_head + 2LL * m->d_head + 2LL * m->d_ff;
+    long long n_in = (long long)m->n_heads * m->d_head + 2LL * m->n_kv_heads * m->d_head + 2LL * m->d_ff;
     if (n_in > (1 << 24) || k_out > (1 << 24) || m->d_model > (1 << 20)) return fail(PD_ERR_SHAPE, "model too large");
     // the kernels address each matrix through a 32-bit buffer descriptor
     if ((long long)m->d_model * n_in >= (1ll << 32) || k_out * m->d_model >= (1ll << 32))
         return fail(PD_ERR_SHAPE, "a projection matrix must be smaller than 4 GiB");
     if (!(m->rope_base > 1.0f) || !(m->ln_eps > 0.0f)) return fail(PD_ERR_SHAPE, "rope_base must exceed 1 and ln_eps must be positive");
     if (s) {
-        s->L = m->n_layers; s->d = m->d_model; s->H = m->n_heads; s->dh = m->d_head; s->F = m->d_ff;
-        s->n_qkv = m->n_heads * m->d_head + 2 * m->d_head;
+        s->L = m->n_layers; s->d = m->d_model; s->H = m->n_heads; s->G = m->n_kv_heads; s->dh = m->d_head; s->F = m->d_ff;
+        s->n_qkv = m->n_heads * m->d_head + 2 * m->n_kv_heads * m->d_head;
         s->n_in = (int)n_in; s->k_out = (int)k_out;
     }
     return PD_OK;
@@ -174,7 +175,7 @@ Workspace workspace_layout(const Shape& s, int B, int L_ctx) {
     return w;
 }
 
-size_t kv_layer_elems(const Shape& s, int B, int L_ctx) { return (size_t)B * L_ctx * s.dh; }
+size_t kv_layer_elems(const Shape& s, int B, int L_ctx) { return (size_t)B * s.G * L_ctx * s.dh; }
 
 // Limits that depend on the batch: the projection operand and the partial-sum slots
 // are also addressed through 32-bit buffer descriptors.
@@ -268,7 +269,7 @@ pd_status run_layers(pd_handle* h, const StepArgs& a, hipStream_t st) {
     const pd::SkqPlan& pl_in = gp.in;
     const pd::SkqPlan& pl_out = gp.out;
     const int blk_o = gp.blk_o, blk_a = gp.blk_a;
-    const int bps = h->opt_bps > 0 ? h->opt_bps : auto_bps(B, a.L_ctx);
+    const int bps = h->opt_bps > 0 ? h->opt_bps : auto_bps(B * s.G, a.L_ctx);
     const int nd = h->act_digits;
     const size_t kv_layer_bytes = kv_layer_elems(s, B, a.L_ctx) * 2;
 
@@ -288,11 +289,11 @@ pd_status run_layers(pd_handle* h, const StepArgs& a, hipStream_t st) {
         PD_TRY_HIP(pd::launch_qgemm(L + pl.w_in, hq, hs, part_in, B, s.d, s.n_in, pl_in, nd, st), "qgemm_in");
         prof_mark(h, PROF_QGEMM_IN, st);
         prof_mark(h, PROF_EPI_IN, st);
-        PD_TRY_HIP(pd::launch_epi_in(part_in, pl_in, s_in, cs, a.positions, B, s.H, s.dh, s.F, a.L_ctx, q,
+        PD_TRY_HIP(pd::launch_epi_in(part_in, pl_in, s_in, cs, a.positions, B, s.H, s.G, s.dh, s.F, a.L_ctx, q,
                                      kc, vc, actq, acts, blk_a, nd, st), "epi_in");
         prof_mark(h, PROF_EPI_IN, st);
         prof_mark(h, PROF_ATTEND, st);
-        PD_TRY_HIP(pd::launch_mqa_attend(q, kc, vc, a.positions, B, s.H, s.dh, a.L_ctx, bps, opart, ml,
+        PD_TRY_HIP(pd::launch_mqa_attend(q, kc, vc, a.positions, B, s.H, s.G, s.dh, a.L_ctx, bps, opart, ml,
                                          nullptr, actq, acts, s.k_out, blk_o, nd, st), "mqa_attend");
         prof_mark(h, PROF_ATTEND, st);
         prof_mark(h, PROF_QGEMM_OUT, st);
@@ -522,7 +523,7 @@ static pd_status kv_convert(pd_handle* h, const void* src, void* dst, int32_t la
     const size_t off = (size_t)layer * kv_layer_elems(h->s, B, L_ctx) * 2;
     const void* s2 = to_library ? src : static_cast<const unsigned char*>(src) + off;
     void* d2 = to_library ? static_cast<unsigned char*>(dst) + off : dst;
-    PD_TRY_HIP(pd::launch_kv_convert(s2, d2, B, L_ctx, h->s.dh, is_v ? 1 : 0, to_library,
+    PD_TRY_HIP(pd::launch_kv_convert(s2, d2, B * h->s.G, L_ctx, h->s.dh, is_v ? 1 : 0, to_library,
                                      static_cast<hipStream_t>(stream)), "kv_convert");
     return PD_OK;
 }
@@ -697,11 +698,11 @@ pd_status pd_mqa_attend(pd_handle* h, int32_t layer, const float* q, const void*
     const Workspace w = workspace_layout(s, B, L_ctx);
     if (workspace_bytes < w.total) return fail(PD_ERR_WORKSPACE, "workspace too small");
     unsigned char* ws = static_cast<unsigned char*>(workspace);
-    const int bps = h->opt_bps > 0 ? h->opt_bps : auto_bps(B, L_ctx);
+    const int bps = h->opt_bps > 0 ? h->opt_bps : auto_bps(B * s.G, L_ctx);
     const size_t off = (size_t)layer * kv_layer_elems(s, B, L_ctx) * 2;
     PD_TRY_HIP(pd::launch_mqa_attend(q, static_cast<const unsigned char*>(k_cache) + off,
                                      static_cast<const unsigned char*>(v_cache) + off, positions, B, s.H,
-                                     s.dh, L_ctx, bps, reinterpret_cast<float*>(ws + w.opart),
+                                     s.G, s.dh, L_ctx, bps, reinterpret_cast<float*>(ws + w.opart),
                                      reinterpret_cast<float*>(ws + w.ml), o, nullptr, nullptr, s.k_out, 1,
                                      h->act_digits, static_cast<hipStream_t>(stream)), "mqa_attend");
     return PD_OK;

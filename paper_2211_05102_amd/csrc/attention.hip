@@ -43,7 +43,7 @@ namespace pd {
 template <int MAXS>
 __global__ __launch_bounds__(256) void mqa_combine_kernel(
     const float* __restrict__ opart, const float* __restrict__ ml,
-    const int32_t* __restrict__ positions, int H, int dh, int L_ctx, int bps, int nsplit,
+    const int32_t* __restrict__ positions, int H, int G, int dh, int L_ctx, int bps, int nsplit,
     float* __restrict__ o, unsigned char* __restrict__ actq, float* __restrict__ acts,
     int k_out, int blk_o, int nd) {
     __shared__ float red[4];
@@ -62,11 +62,13 @@ __global__ __launch_bounds__(256) void mqa_combine_kernel(
         if (j < c_hi) {
             const int idx = j * QCHUNK + 2 * lane;  // idx and idx + 1 lie in the same head
             const int h = idx / dh, c = idx - h * dh;
-            const size_t row0 = (size_t)b * nsplit * H + h;
+            // K/V head h / per of row b is pseudo-sequence b*G + h/per; it holds `per` query heads
+            const int per = H / G;
+            const size_t row0 = ((size_t)b * G + h / per) * nsplit * per + h % per;
             f32x2 mlv[MAXS], ov[MAXS];
 #pragma unroll
             for (int s = 0; s < MAXS; s++) {
-                const size_t row = row0 + (size_t)(s < live ? s : live - 1) * H;
+                const size_t row = row0 + (size_t)(s < live ? s : live - 1) * per;
                 mlv[s] = *reinterpret_cast<const f32x2*>(ml + row * 2);
                 ov[s] = *reinterpret_cast<const f32x2*>(opart + row * dh + c);
             }
@@ -109,7 +111,7 @@ __global__ __launch_bounds__(256) void mqa_combine_kernel(
 // the same with a run-time number of splits (long contexts with small splits)
 __global__ __launch_bounds__(256) void mqa_combine_any_kernel(
     const float* __restrict__ opart, const float* __restrict__ ml,
-    const int32_t* __restrict__ positions, int H, int dh, int L_ctx, int bps, int nsplit,
+    const int32_t* __restrict__ positions, int H, int G, int dh, int L_ctx, int bps, int nsplit,
     float* __restrict__ o, unsigned char* __restrict__ actq, float* __restrict__ acts,
     int k_out, int blk_o, int nd) {
     __shared__ float red[4];
@@ -128,12 +130,13 @@ __global__ __launch_bounds__(256) void mqa_combine_any_kernel(
         if (j < c_hi) {
             const int idx = j * QCHUNK + 2 * lane;
             const int h = idx / dh, c = idx - h * dh;
-            const size_t row0 = (size_t)b * nsplit * H + h;
+            const int per = H / G;
+            const size_t row0 = ((size_t)b * G + h / per) * nsplit * per + h % per;
             float m_all = -INFINITY;
-            for (int s = 0; s < live; s++) m_all = fmaxf(m_all, ml[(row0 + (size_t)s * H) * 2]);
+            for (int s = 0; s < live; s++) m_all = fmaxf(m_all, ml[(row0 + (size_t)s * per) * 2]);
             float n0 = 0.f, n1 = 0.f, den = 0.f;
             for (int s = 0; s < live; s++) {
-                const size_t row = row0 + (size_t)s * H;
+                const size_t row = row0 + (size_t)s * per;
                 const float w = __builtin_amdgcn_exp2f(ml[row * 2] - m_all);
                 den += w * ml[row * 2 + 1];
                 const f32x2 ov = *reinterpret_cast<const f32x2*>(opart + row * dh + c);
@@ -166,7 +169,7 @@ __global__ __launch_bounds__(256) void mqa_combine_any_kernel(
 template <int DH>
 __global__ __launch_bounds__(256) void mqa_attend_kernel(
     const float* __restrict__ q, const uint4* __restrict__ kc, const uint4* __restrict__ vc,
-    const int32_t* __restrict__ positions, int H, int L_ctx, int bps, int nsplit,
+    const int32_t* __restrict__ positions, int H, int G, int L_ctx, int bps, int nsplit,
     float* __restrict__ opart, float* __restrict__ ml, float scale_log2e) {
     constexpr int KJ = DH / 16;  // MFMA steps of the q.K product
     constexpr int DB = DH / 32;  // 32-channel blocks of the output
@@ -182,7 +185,8 @@ __global__ __launch_bounds__(256) void mqa_attend_kernel(
     // otherwise every load below is wrapped in a loop over the "distinct" values)
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int g = lane >> 5, l32 = lane & 31;
-    const int P = positions[b];
+    // b is a pseudo-sequence: K/V head b % G of batch row b / G, with H query heads
+    const int P = positions[b / G];
     if (P < 0 || P >= L_ctx) return;  // reported by the prep kernel; nothing is read or written
     const int nblk = (P >> 5) + 1;
     const int blk0 = split * bps;
@@ -420,25 +424,29 @@ __global__ __launch_bounds__(256) void kv_convert_kernel(const uint16_t* __restr
     else dst[idx] = src[lib];
 }
 
+// G K/V heads per row (1 = multiquery, H = multihead): the attend kernel runs on B*G
+// pseudo-sequences of H/G query heads each; q [B][H][dh] and o [B][H*dh] need no reordering.
 hipError_t launch_mqa_attend(const float* q, const void* kc_layer, const void* vc_layer,
-                             const int32_t* positions, int B, int H, int dh, int L_ctx, int bps,
+                             const int32_t* positions, int B, int H, int G, int dh, int L_ctx, int bps,
                              float* opart, float* ml, float* o, void* actq, float* acts,
                              int k_out, int blk_o, int nd, hipStream_t stream) {
     if (blk_o < 1 || blk_o > 16) return hipErrorInvalidValue;
+    if (G < 1 || H % G || H / G > 32 || (long long)B * G > 65535) return hipErrorInvalidValue;
+    const int per = H / G;
     const int nblk_cap = L_ctx / 32;
     const int nsplit = (nblk_cap + bps - 1) / bps;
     const float scale_log2e = 1.4426950408889634f / sqrtf((float)dh);
-    dim3 grid(nsplit, B), block(256);
+    dim3 grid(nsplit, B * G), block(256);
     const uint4* k4 = reinterpret_cast<const uint4*>(kc_layer);
     const uint4* v4 = reinterpret_cast<const uint4*>(vc_layer);
     if (dh == 256)
-        mqa_attend_kernel<256><<<grid, block, 0, stream>>>(q, k4, v4, positions, H, L_ctx, bps, nsplit,
+        mqa_attend_kernel<256><<<grid, block, 0, stream>>>(q, k4, v4, positions, per, G, L_ctx, bps, nsplit,
                                                            opart, ml, scale_log2e);
     else if (dh == 128)
-        mqa_attend_kernel<128><<<grid, block, 0, stream>>>(q, k4, v4, positions, H, L_ctx, bps, nsplit,
+        mqa_attend_kernel<128><<<grid, block, 0, stream>>>(q, k4, v4, positions, per, G, L_ctx, bps, nsplit,
                                                            opart, ml, scale_log2e);
     else if (dh == 64)
-        mqa_attend_kernel<64><<<grid, block, 0, stream>>>(q, k4, v4, positions, H, L_ctx, bps, nsplit,
+        mqa_attend_kernel<64><<<grid, block, 0, stream>>>(q, k4, v4, positions, per, G, L_ctx, bps, nsplit,
                                                           opart, ml, scale_log2e);
     else
         return hipErrorInvalidValue;
@@ -446,7 +454,7 @@ hipError_t launch_mqa_attend(const float* q, const void* kc_layer, const void* v
     if (e != hipSuccess) return e;
     dim3 cgrid((H * dh / 128 + blk_o - 1) / blk_o, B);
     unsigned char* aq = reinterpret_cast<unsigned char*>(actq);
-#define PD_COMB(K) K<<<cgrid, block, 0, stream>>>(opart, ml, positions, H, dh, L_ctx, bps, nsplit, o, aq, acts, k_out, blk_o, nd)
+#define PD_COMB(K) K<<<cgrid, block, 0, stream>>>(opart, ml, positions, H, G, dh, L_ctx, bps, nsplit, o, aq, acts, k_out, blk_o, nd)
     if (nsplit <= 4) PD_COMB(mqa_combine_kernel<4>);
     else if (nsplit <= 8) PD_COMB(mqa_combine_kernel<8>);
     else if (nsplit <= 16) PD_COMB(mqa_combine_kernel<16>);

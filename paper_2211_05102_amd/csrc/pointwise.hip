@@ -97,7 +97,8 @@ __device__ __forceinline__ float sum_partials(const float* __restrict__ part, co
 }
 
 // Section A (blockIdx.x < n_blocks_a): one item per thread over H*dh/2 q pairs |
-// dh/2 k pairs | dh v elements.  Section B: one workgroup per scale block of the
+// G*dh/2 k pairs | G*dh v elements (G K/V heads: 1 = multiquery, H = multihead; K/V head j
+// of row b is pseudo-sequence b*G + j of the cache).  Section B: one workgroup per scale block of the
 // SwiGLU output (blk_a chunks of 128, at most 64): each wave takes every fourth
 // chunk, the block maximum fixes one power-of-two scale, and the digits go into
 // the operand of the output projection (chunks H*dh/128 ... of the row).
@@ -105,15 +106,15 @@ __device__ __forceinline__ float sum_partials(const float* __restrict__ part, co
 // (32 gate, 32 up).  Cache element offsets follow the library block layouts.
 __global__ __launch_bounds__(256) void epi_in_kernel(
     const float* __restrict__ part, SkqPlan pl, const float* __restrict__ scale,
-    const float* __restrict__ cs, const int32_t* __restrict__ positions, int B, int H, int dh, int F,
+    const float* __restrict__ cs, const int32_t* __restrict__ positions, int B, int H, int G, int dh, int F,
     int L_ctx, int n_blocks_a, float* __restrict__ q, uint16_t* __restrict__ kc,
     uint16_t* __restrict__ vc, unsigned char* __restrict__ actq, float* __restrict__ acts,
     int blk_a, int nd) {
     __shared__ float red[4];
     const int b = blockIdx.y;
     const int half = dh >> 1;
-    const int n_q = H * half, n_k = half, n_v = dh;
-    const int n_qkv = H * dh + 2 * dh;
+    const int n_q = H * half, n_k = G * half, n_v = G * dh;
+    const int n_qkv = H * dh + 2 * G * dh;
     const int N = n_qkv + 2 * F;
     const int k_out = H * dh + F;
     const size_t stride = (size_t)pl.rows * N, rowoff = (size_t)b * N;
@@ -168,8 +169,8 @@ __global__ __launch_bounds__(256) void epi_in_kernel(
         // rotation pair (i, i + dh/2) of a q head or of k
         const bool is_k = item >= n_q;
         const int pi = is_k ? item - n_q : item;
-        const int head = is_k ? 0 : pi / half, i = pi % half;
-        const int col = (is_k ? H * dh : head * dh) + i;
+        const int head = pi / half, i = pi % half;  // query head, or K/V head
+        const int col = (is_k ? H * dh : 0) + head * dh + i;
         float lo = scale[col] * sum_partials(part, pl, stride, rowoff + col, col);
         float hi = scale[col + half] * sum_partials(part, pl, stride, rowoff + col + half, col + half);
         const float cn = cs[((size_t)b * half + i) * 2], sn = cs[((size_t)b * half + i) * 2 + 1];
@@ -179,7 +180,7 @@ __global__ __launch_bounds__(256) void epi_in_kernel(
             qrow[i] = rlo;
             qrow[i + half] = rhi;
         } else if (ok) {
-            const size_t blk = ((size_t)b * (L_ctx >> 5) + (P >> 5)) * 32 * dh;
+            const size_t blk = (((size_t)b * G + head) * (L_ctx >> 5) + (P >> 5)) * 32 * dh;
             const int tt = P & 31;
             int c = i;
             kc[blk + (((size_t)(c >> 4) * 2 + ((c & 15) >> 3)) * 32 + tt) * 8 + (c & 7)] = to_bf16(rlo);
@@ -187,11 +188,12 @@ __global__ __launch_bounds__(256) void epi_in_kernel(
             kc[blk + (((size_t)(c >> 4) * 2 + ((c & 15) >> 3)) * 32 + tt) * 8 + (c & 7)] = to_bf16(rhi);
         }
     } else if (item < n_q + n_k + n_v) {
-        const int c = item - n_q - n_k;
-        const int col = H * dh + dh + c;
+        const int cv = item - n_q - n_k;
+        const int head = cv / dh, c = cv - head * dh;
+        const int col = H * dh + G * dh + cv;
         float v = scale[col] * sum_partials(part, pl, stride, rowoff + col, col);
         if (ok) {
-            const size_t blk = ((size_t)b * (L_ctx >> 5) + (P >> 5)) * 32 * dh;
+            const size_t blk = (((size_t)b * G + head) * (L_ctx >> 5) + (P >> 5)) * 32 * dh;
             const int tt = P & 31;
             vc[blk + ((((size_t)(c >> 5) * 2 + (tt >> 4)) * 2 + ((tt & 7) >> 2)) * 32 + (c & 31)) * 8 +
                4 * ((tt & 15) >> 3) + (tt & 3)] = to_bf16(v);
@@ -438,15 +440,15 @@ hipError_t launch_ln_first(const uint16_t* x_in, const float* gamma, int B, int 
 }
 
 hipError_t launch_epi_in(const float* part, SkqPlan pl, const float* scale, const float* cs,
-                         const int32_t* positions, int B, int H, int dh, int F, int L_ctx,
+                         const int32_t* positions, int B, int H, int G, int dh, int F, int L_ctx,
                          float* q, void* kc_layer, void* vc_layer, void* actq, float* acts,
                          int blk_a, int nd, hipStream_t stream) {
     if (blk_a < 1 || blk_a > 64) return hipErrorInvalidValue;
-    const int items = H * dh / 2 + dh / 2 + dh;
+    const int items = H * dh / 2 + G * dh / 2 + G * dh;
     const int n_blocks_a = (items + 255) / 256;
     const int n_blocks_b = (F / 128 + blk_a - 1) / blk_a;
     epi_in_kernel<<<dim3(n_blocks_a + n_blocks_b, B), dim3(256), 0, stream>>>(
-        part, pl, scale, cs, positions, B, H, dh, F, L_ctx, n_blocks_a, q,
+        part, pl, scale, cs, positions, B, H, G, dh, F, L_ctx, n_blocks_a, q,
         reinterpret_cast<uint16_t*>(kc_layer), reinterpret_cast<uint16_t*>(vc_layer),
         reinterpret_cast<unsigned char*>(actq), acts, blk_a, nd);
     return hipGetLastError();

@@ -40,8 +40,9 @@ class DeviceStack:
             self.dec.pack_layer(wts, self.layer_view(l))
             k, v = synth.kv_layer(w, l, device, batch=self.B)
             if poison_unused:  # slots past the position must never be read
-                k = torch.where(live[:, :, None], k, torch.full_like(k, float("nan")))
-                v = torch.where(live[:, :, None], v, torch.full_like(v, float("inf")))
+                lv = live[:, :, None] if k.dim() == 3 else live[:, None, :, None]
+                k = torch.where(lv, k, torch.full_like(k, float("nan")))
+                v = torch.where(lv, v, torch.full_like(v, float("inf")))
             self.dec.kv_import(k, self.k_cache, l, False)
             self.dec.kv_import(v, self.v_cache, l, True)
             if on_layer is not None:
@@ -58,7 +59,9 @@ class DeviceStack:
         return self.x_out
 
     def export_kv(self, layer: int):
-        k = torch.empty(self.B, self.w.l_ctx, self.w.d_head, dtype=torch.bfloat16, device=self.device)
+        G = self.w.n_kv_heads
+        shape = (self.B, self.w.l_ctx, self.w.d_head) if G == 1 else (self.B, G, self.w.l_ctx, self.w.d_head)
+        k = torch.empty(*shape, dtype=torch.bfloat16, device=self.device)
         v = torch.empty_like(k)
         self.dec.kv_export(self.k_cache, k, layer, False)
         self.dec.kv_export(self.v_cache, v, layer, True)

@@ -51,7 +51,7 @@ def test_sizes(binding):
 def test_bad_descriptions_are_rejected(binding):
     from workloads import WORKLOADS
     w = WORKLOADS["c1_tiny"]
-    for bad in (w.with_(d_model=200), w.with_(d_head=96), w.with_(n_heads=33), w.with_(n_kv_heads=4),
+    for bad in (w.with_(d_model=200), w.with_(d_head=96), w.with_(n_heads=33), w.with_(n_kv_heads=3),
                 w.with_(d_ff=1000), w.with_(n_layers=0), w.with_(d_ff=1056)):
         with pytest.raises(binding.PdError) as e:
             binding.Decoder(bad)

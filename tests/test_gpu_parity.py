@@ -184,14 +184,17 @@ def check_every_cache_slot(w, st, pos_t, poison):
     t = torch.arange(L, device="cuda")[None, :]
     p = pos_t.to("cuda").long()[:, None]
     live, at_p = t <= p, t == p
+    if w.n_kv_heads > 1:  # caches are [B, G, L, dh]: the same slot of every K/V head
+        live = live[:, None, :].expand(B, w.n_kv_heads, L)
+        at_p = at_p[:, None, :].expand(B, w.n_kv_heads, L)
     for l in range(w.n_layers):
         k0, v0 = synth.kv_layer(w, l, "cuda", batch=B)
         if poison:
-            k0 = torch.where(live[:, :, None], k0, torch.full_like(k0, float("nan")))
-            v0 = torch.where(live[:, :, None], v0, torch.full_like(v0, float("inf")))
+            k0 = torch.where(live[..., None], k0, torch.full_like(k0, float("nan")))
+            v0 = torch.where(live[..., None], v0, torch.full_like(v0, float("inf")))
         kg, vg = st.export_kv(l)
         for name, got, ref in (("K", kg, k0), ("V", vg, v0)):
-            changed = (got.view(torch.int16) != ref.view(torch.int16)).any(dim=2)  # [B, L]
+            changed = (got.view(torch.int16) != ref.view(torch.int16)).any(dim=-1)  # [B, (G,) L]
             if l % 16 == 15 and name == "V":
                 print(f"[parity] {w.name}: every-slot cache check through layer {l + 1}/{w.n_layers}", flush=True)
             if not torch.equal(changed, at_p):
@@ -208,12 +211,15 @@ def check_cache_append(w, st, kcs_after, vcs_after, kcs_before, vcs_before, rows
         kg, vg = st.export_kv(l)
         kg, vg = bits_np(kg[rows]), bits_np(vg[rows])
         for name, gpu, before, after in (("K", kg, kcs_before[l], kcs_after[l]), ("V", vg, vcs_before[l], vcs_after[l])):
-            changed = np.argwhere((gpu != before).any(axis=2))
-            want = np.array([[i, int(positions[r])] for i, r in enumerate(rows)])
+            changed = np.argwhere((gpu != before).any(axis=-1))
+            if gpu.ndim == 3:
+                want = np.array([[i, int(positions[r])] for i, r in enumerate(rows)])
+            else:  # [rows, G, L, dh]
+                want = np.array([[i, j, int(positions[r])] for i, r in enumerate(rows) for j in range(gpu.shape[1])])
             assert np.array_equal(changed, want), (name, l, changed[:8], want[:8])
             for i, r in enumerate(rows):
                 p = int(positions[r])
-                a, b = widen(gpu[i, p]), widen(after[i, p])
+                a, b = widen(gpu[i, ..., p, :]), widen(after[i, ..., p, :])
                 assert np.max(np.abs(a - b) / np.maximum(1.0, np.abs(b))) <= MAX_SCALED, (name, l, r)
 
 
@@ -338,6 +344,21 @@ def test_decode_step_random_small_shapes(pd, shape):
     w = Workload("rand", L_, d, H, dh, F, B, L, positions="ragged", pos_lo=0, pos_hi=L)
     st, scaled, rel, _, _ = run_stack_parity(pd, w, name=f"rand{shape}")
     assert scaled <= MAX_SCALED and rel <= REL_L2, (scaled, rel)
+
+
+@pytest.mark.parametrize("shape", [
+    # (layers, d, H, G, dh, F, B, L): multihead (G = H) at all three head sizes, ragged batches
+    (2, 512, 8, 8, 64, 512, 5, 96), (2, 768, 6, 6, 128, 384, 33, 160), (1, 1024, 4, 4, 256, 1024, 7, 64),
+    (2, 6144, 48, 48, 128, 1024, 3, 128),
+])
+def test_decode_step_multihead_small_shapes(pd, shape):
+    # the multihead baseline of Section 3.3 / Section 4.2: one K/V head per query head, including
+    # the head count and head size of the 540B multihead variant (48 x 128)
+    L_, d, H, G, dh, F, B, L = shape
+    w = Workload("mha", L_, d, H, dh, F, B, L, positions="ragged", pos_lo=0, pos_hi=L, n_kv_heads=G)
+    st, scaled, rel, _, _ = run_stack_parity(pd, w, name=f"mha{shape}")
+    assert scaled <= MAX_SCALED and rel <= REL_L2, (scaled, rel)
+    assert_bitwise_repeatable(st, st.x_out)
 
 
 def test_decode_layer_partial_without_residual(pd):
