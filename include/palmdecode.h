@@ -178,6 +178,29 @@ pd_status pd_decode_step(pd_handle* h, const void* packed_weights, void* k_cache
                          uint16_t* x_out, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Prefill, whole or incremental (Section 2.2: the input tokens are all present at the
+ * start and run through the model in parallel; Section 3.5: incremental processing
+ * of sequences during prefill).  n_tokens token rows, each with the cache row
+ * (sequence) it belongs to and its position; every row appends its K/V at
+ * (seq_ids[r], positions[r]) and attends over slots 0..positions[r] of that cache
+ * row -- causal attention, since tokens after it sit at higher slots.  Rows are
+ * processed in chunks of 256 in array order; a token's predecessors must be in the
+ * cache already or come no later than the token's own chunk (e.g. rows ordered by
+ * position), and no (sequence, position) pair may occur twice in a chunk.  Sequences
+ * may already hold cached tokens (incremental prefill) and may have different
+ * lengths.  The caches have `cache_rows` rows of capacity L_ctx
+ * (pd_kv_cache_bytes(desc, cache_rows, L_ctx)); workspace >=
+ * pd_workspace_bytes(desc, min(n_tokens, 256), L_ctx).  x_out [n_tokens][d_model] bf16
+ * is the hidden state of every token after the last block (may alias x_in).  Device
+ * data that is out of range (position, sequence id) skips the row and raises the flag
+ * pd_check_async() reports for the last chunk.
+ */
+pd_status pd_prefill(pd_handle* h, const void* packed_weights, void* k_cache, void* v_cache,
+                     const uint16_t* x_in, const int32_t* seq_ids, const int32_t* positions,
+                     int32_t n_tokens, int32_t cache_rows, int32_t L_ctx, uint16_t* x_out,
+                     void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * One layer of the step, for per-layer checks and for a weight shard's
  * unreduced partial (Section 3.2.1: a 1D weight-stationary shard over heads
  * and d_ff produces a partial sum that still needs a cross-chip reduction).

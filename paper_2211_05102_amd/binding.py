@@ -26,7 +26,7 @@ EXPORTS = [
     "pd_check_async", "pd_qgemm_workspace_bytes", "pd_qgemm_plan", "pd_qgemm", "pd_mqa_attend",
     "pd_graph_capture", "pd_graph_replay", "pd_graph_release", "pd_profile_read",
     "pd_packed_head_bytes", "pd_head_workspace_bytes", "pd_generate_workspace_bytes", "pd_pack_head",
-    "pd_head_logits", "pd_sample", "pd_generate",
+    "pd_head_logits", "pd_sample", "pd_generate", "pd_prefill",
 ]
 
 
@@ -229,6 +229,15 @@ class Decoder:
         _check(lib().pd_decode_step_static(self._h, _ptr(packed), _ptr(k_cache), _ptr(v_cache), _ptr(x_in),
                                            _ptr(positions), ctypes.c_int32(B), ctypes.c_int32(L_ctx),
                                            _ptr(x_out), _stream(stream)))
+
+    def prefill(self, packed, k_cache, v_cache, x_in, seq_ids, positions, cache_rows, L_ctx, x_out, workspace,
+                stream=None) -> None:
+        n = x_in.shape[0]
+        assert seq_ids.dtype == torch.int32 and positions.dtype == torch.int32
+        _check(lib().pd_prefill(self._h, _ptr(packed), _ptr(k_cache), _ptr(v_cache), _ptr(x_in), _ptr(seq_ids),
+                                _ptr(positions), ctypes.c_int32(n), ctypes.c_int32(cache_rows),
+                                ctypes.c_int32(L_ctx), _ptr(x_out), _ptr(workspace),
+                                ctypes.c_size_t(workspace.numel() * workspace.element_size()), _stream(stream)))
 
     def decode_layer(self, layer, packed_layer, k_cache, v_cache, x_in, positions, L_ctx, y_out,
                      add_residual, workspace, stream=None) -> None:

@@ -101,6 +101,7 @@ int auto_bps(int B, int L_ctx) {
 // units -- so results do not depend on where the code runs and the workspace can
 // be sized on the host.
 constexpr int PD_GEMM_WORKGROUPS = 256;
+constexpr int PD_PREFILL_CHUNK = 256;  // token rows per pass of the stack in pd_prefill
 struct GemmPlans {
     pd::SkqPlan in, out;
     int slots_in, slots_out;
@@ -240,6 +241,8 @@ struct StepArgs {
     int add_residual;
     int layer0, n_run;  // cache layer index of the first layer, number of layers to run
     unsigned char* ws;
+    const int32_t* seq = nullptr;  // cache row of each token row (NULL: row b uses cache row b)
+    int cache_rows = 0;            // rows of the caches (0: B)
 };
 
 pd_status run_layers(pd_handle* h, const StepArgs& a, hipStream_t st) {
@@ -271,9 +274,10 @@ pd_status run_layers(pd_handle* h, const StepArgs& a, hipStream_t st) {
     const int blk_o = gp.blk_o, blk_a = gp.blk_a;
     const int bps = h->opt_bps > 0 ? h->opt_bps : auto_bps(B * s.G, a.L_ctx);
     const int nd = h->act_digits;
-    const size_t kv_layer_bytes = kv_layer_elems(s, B, a.L_ctx) * 2;
+    const int cache_rows = a.cache_rows > 0 ? a.cache_rows : B;
+    const size_t kv_layer_bytes = kv_layer_elems(s, cache_rows, a.L_ctx) * 2;
 
-    PD_TRY_HIP(pd::launch_prep(a.positions, B, a.L_ctx, s.dh, h->desc.rope_base, cs, flag, st), "prep");
+    PD_TRY_HIP(pd::launch_prep(a.positions, B, a.L_ctx, s.dh, h->desc.rope_base, cs, flag, a.seq, cache_rows, st), "prep");
     PD_TRY_HIP(pd::launch_skq_table(pl_in, reinterpret_cast<int*>(a.ws + w.nseg_in), st), "segment table (in)");
     PD_TRY_HIP(pd::launch_skq_table(pl_out, reinterpret_cast<int*>(a.ws + w.nseg_out), st), "segment table (out)");
     for (int i = 0; i < a.n_run; i++) {
@@ -289,11 +293,11 @@ pd_status run_layers(pd_handle* h, const StepArgs& a, hipStream_t st) {
         PD_TRY_HIP(pd::launch_qgemm(L + pl.w_in, hq, hs, part_in, B, s.d, s.n_in, pl_in, nd, st), "qgemm_in");
         prof_mark(h, PROF_QGEMM_IN, st);
         prof_mark(h, PROF_EPI_IN, st);
-        PD_TRY_HIP(pd::launch_epi_in(part_in, pl_in, s_in, cs, a.positions, B, s.H, s.G, s.dh, s.F, a.L_ctx, q,
+        PD_TRY_HIP(pd::launch_epi_in(part_in, pl_in, s_in, cs, a.positions, a.seq, cache_rows, B, s.H, s.G, s.dh, s.F, a.L_ctx, q,
                                      kc, vc, actq, acts, blk_a, nd, st), "epi_in");
         prof_mark(h, PROF_EPI_IN, st);
         prof_mark(h, PROF_ATTEND, st);
-        PD_TRY_HIP(pd::launch_mqa_attend(q, kc, vc, a.positions, B, s.H, s.G, s.dh, a.L_ctx, bps, opart, ml,
+        PD_TRY_HIP(pd::launch_mqa_attend(q, kc, vc, a.positions, a.seq, cache_rows, B, s.H, s.G, s.dh, a.L_ctx, bps, opart, ml,
                                          nullptr, actq, acts, s.k_out, blk_o, nd, st), "mqa_attend");
         prof_mark(h, PROF_ATTEND, st);
         prof_mark(h, PROF_QGEMM_OUT, st);
@@ -572,6 +576,35 @@ pd_status pd_decode_step_static(pd_handle* h, const void* packed_weights, void* 
     return run_layers(h, a, static_cast<hipStream_t>(stream));
 }
 
+pd_status pd_prefill(pd_handle* h, const void* packed_weights, void* k_cache, void* v_cache,
+                     const uint16_t* x_in, const int32_t* seq_ids, const int32_t* positions, int32_t n_tokens,
+                     int32_t cache_rows, int32_t L_ctx, uint16_t* x_out, void* workspace,
+                     size_t workspace_bytes, void* stream) {
+    if (!h) return fail(PD_ERR_NULL, "handle is NULL");
+    if (!seq_ids) return fail(PD_ERR_NULL, "NULL device pointer");
+    if (n_tokens < 1 || n_tokens > (1 << 24)) return fail(PD_ERR_SHAPE, "n_tokens must be in 1..2^24");
+    if (cache_rows < 1 || cache_rows > 65535) return fail(PD_ERR_SHAPE, "cache_rows must be in 1..65535");
+    // the stack runs on chunks of up to PD_PREFILL_CHUNK token rows: every chunk streams the weights once
+    const int chunk = n_tokens < PD_PREFILL_CHUNK ? n_tokens : PD_PREFILL_CHUNK;
+    pd_status rc = check_step_args(h, packed_weights, k_cache, v_cache, x_in, positions, chunk, L_ctx, x_out,
+                                   workspace, workspace_bytes);
+    if (rc != PD_OK) return rc;
+    if (!aligned(seq_ids, 4)) return fail(PD_ERR_ALIGN, "seq_ids must be 4-byte aligned");
+    const size_t d = (size_t)h->s.d;
+    for (int t0 = 0; t0 < n_tokens; t0 += PD_PREFILL_CHUNK) {
+        const int rows = n_tokens - t0 < PD_PREFILL_CHUNK ? n_tokens - t0 : PD_PREFILL_CHUNK;
+        if ((rc = check_limits(h->s, rows)) != PD_OK) return rc;
+        if (workspace_bytes < workspace_layout(h->s, rows, L_ctx).total) return fail(PD_ERR_WORKSPACE, "workspace too small");
+        StepArgs a{static_cast<const unsigned char*>(packed_weights), k_cache, v_cache, x_in + t0 * d,
+                   positions + t0, rows, L_ctx, x_out + t0 * d, nullptr, 1, 0, h->s.L,
+                   static_cast<unsigned char*>(workspace)};
+        a.seq = seq_ids + t0;
+        a.cache_rows = cache_rows;
+        if ((rc = run_layers(h, a, static_cast<hipStream_t>(stream))) != PD_OK) return rc;
+    }
+    return PD_OK;
+}
+
 pd_status pd_decode_layer(pd_handle* h, int32_t layer, const void* packed_layer, void* k_cache,
                           void* v_cache, const uint16_t* x_in, const int32_t* positions, int32_t B,
                           int32_t L_ctx, float* y_out, int32_t add_residual, void* workspace,
@@ -701,7 +734,7 @@ pd_status pd_mqa_attend(pd_handle* h, int32_t layer, const float* q, const void*
     const int bps = h->opt_bps > 0 ? h->opt_bps : auto_bps(B * s.G, L_ctx);
     const size_t off = (size_t)layer * kv_layer_elems(s, B, L_ctx) * 2;
     PD_TRY_HIP(pd::launch_mqa_attend(q, static_cast<const unsigned char*>(k_cache) + off,
-                                     static_cast<const unsigned char*>(v_cache) + off, positions, B, s.H,
+                                     static_cast<const unsigned char*>(v_cache) + off, positions, nullptr, B, B, s.H,
                                      s.G, s.dh, L_ctx, bps, reinterpret_cast<float*>(ws + w.opart),
                                      reinterpret_cast<float*>(ws + w.ml), o, nullptr, nullptr, s.k_out, 1,
                                      h->act_digits, static_cast<hipStream_t>(stream)), "mqa_attend");

@@ -169,8 +169,8 @@ __global__ __launch_bounds__(256) void mqa_combine_any_kernel(
 template <int DH>
 __global__ __launch_bounds__(256) void mqa_attend_kernel(
     const float* __restrict__ q, const uint4* __restrict__ kc, const uint4* __restrict__ vc,
-    const int32_t* __restrict__ positions, int H, int G, int L_ctx, int bps, int nsplit,
-    float* __restrict__ opart, float* __restrict__ ml, float scale_log2e) {
+    const int32_t* __restrict__ positions, const int32_t* __restrict__ seq, int cache_rows, int H, int G,
+    int L_ctx, int bps, int nsplit, float* __restrict__ opart, float* __restrict__ ml, float scale_log2e) {
     constexpr int KJ = DH / 16;  // MFMA steps of the q.K product
     constexpr int DB = DH / 32;  // 32-channel blocks of the output
     constexpr int BLK_U4 = 4 * DH;  // uint4 per 32-token block (K and V alike)
@@ -185,9 +185,12 @@ __global__ __launch_bounds__(256) void mqa_attend_kernel(
     // otherwise every load below is wrapped in a loop over the "distinct" values)
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int g = lane >> 5, l32 = lane & 31;
-    // b is a pseudo-sequence: K/V head b % G of batch row b / G, with H query heads
+    // b is a pseudo-sequence: K/V head b % G of token row b / G, with H query heads; the
+    // row's keys and values live in cache row seq[b / G] (the row itself without a map)
     const int P = positions[b / G];
-    if (P < 0 || P >= L_ctx) return;  // reported by the prep kernel; nothing is read or written
+    const int sb = seq ? seq[b / G] : b / G;
+    if (P < 0 || P >= L_ctx || sb < 0 || sb >= cache_rows) return;  // reported by the prep kernel; nothing is read or written
+    const size_t cache_seq = (size_t)sb * G + b % G;
     const int nblk = (P >> 5) + 1;
     const int blk0 = split * bps;
     const int blk1 = blk0 + bps < nblk ? blk0 + bps : nblk;
@@ -198,9 +201,9 @@ __global__ __launch_bounds__(256) void mqa_attend_kernel(
     // ends: the software pipeline below always asks for the next block, and a read
     // past the end returns zeros without touching memory.
     const __amdgpu_buffer_rsrc_t k_rs = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<uint4*>(kc + (size_t)b * nblk_cap * BLK_U4), 0, blk1 * BLK_U4 * 16, 0x00020000);
+        const_cast<uint4*>(kc + cache_seq * nblk_cap * BLK_U4), 0, blk1 * BLK_U4 * 16, 0x00020000);
     const __amdgpu_buffer_rsrc_t v_rs = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<uint4*>(vc + (size_t)b * nblk_cap * BLK_U4), 0, blk1 * BLK_U4 * 16, 0x00020000);
+        const_cast<uint4*>(vc + cache_seq * nblk_cap * BLK_U4), 0, blk1 * BLK_U4 * 16, 0x00020000);
     const uint32_t lane16 = lane * 16;
 
     float m_run = -INFINITY, l_run = 0.f;
@@ -427,7 +430,8 @@ __global__ __launch_bounds__(256) void kv_convert_kernel(const uint16_t* __restr
 // G K/V heads per row (1 = multiquery, H = multihead): the attend kernel runs on B*G
 // pseudo-sequences of H/G query heads each; q [B][H][dh] and o [B][H*dh] need no reordering.
 hipError_t launch_mqa_attend(const float* q, const void* kc_layer, const void* vc_layer,
-                             const int32_t* positions, int B, int H, int G, int dh, int L_ctx, int bps,
+                             const int32_t* positions, const int32_t* seq, int cache_rows, int B, int H,
+                             int G, int dh, int L_ctx, int bps,
                              float* opart, float* ml, float* o, void* actq, float* acts,
                              int k_out, int blk_o, int nd, hipStream_t stream) {
     if (blk_o < 1 || blk_o > 16) return hipErrorInvalidValue;
@@ -440,13 +444,13 @@ hipError_t launch_mqa_attend(const float* q, const void* kc_layer, const void* v
     const uint4* k4 = reinterpret_cast<const uint4*>(kc_layer);
     const uint4* v4 = reinterpret_cast<const uint4*>(vc_layer);
     if (dh == 256)
-        mqa_attend_kernel<256><<<grid, block, 0, stream>>>(q, k4, v4, positions, per, G, L_ctx, bps, nsplit,
+        mqa_attend_kernel<256><<<grid, block, 0, stream>>>(q, k4, v4, positions, seq, cache_rows, per, G, L_ctx, bps, nsplit,
                                                            opart, ml, scale_log2e);
     else if (dh == 128)
-        mqa_attend_kernel<128><<<grid, block, 0, stream>>>(q, k4, v4, positions, per, G, L_ctx, bps, nsplit,
+        mqa_attend_kernel<128><<<grid, block, 0, stream>>>(q, k4, v4, positions, seq, cache_rows, per, G, L_ctx, bps, nsplit,
                                                            opart, ml, scale_log2e);
     else if (dh == 64)
-        mqa_attend_kernel<64><<<grid, block, 0, stream>>>(q, k4, v4, positions, per, G, L_ctx, bps, nsplit,
+        mqa_attend_kernel<64><<<grid, block, 0, stream>>>(q, k4, v4, positions, seq, cache_rows, per, G, L_ctx, bps, nsplit,
                                                           opart, ml, scale_log2e);
     else
         return hipErrorInvalidValue;

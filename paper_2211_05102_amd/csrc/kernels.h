@@ -28,19 +28,22 @@ hipError_t launch_qgemm_reduce(const float* part, const float* scale, float* out
 
 // ---- attention.hip
 hipError_t launch_mqa_attend(const float* q, const void* kc_layer, const void* vc_layer,
-                             const int32_t* positions, int B, int H, int G, int dh, int L_ctx, int bps,
+                             const int32_t* positions, const int32_t* seq, int cache_rows, int B, int H,
+                             int G, int dh, int L_ctx, int bps,
                              float* opart, float* ml, float* o, void* actq, float* acts,
                              int k_out, int blk_o, int nd, hipStream_t stream);
 hipError_t launch_kv_convert(const void* src, void* dst, int B, int L_ctx, int dh, int is_v,
                              int to_library, hipStream_t stream);
 
 // ---- pointwise.hip
+// `seq` (may be NULL = identity): cache row of each token row; `cache_rows` = rows of the cache
 hipError_t launch_prep(const int32_t* positions, int B, int L_ctx, int dh, float rope_base,
-                       float* cs, int32_t* flag, hipStream_t stream);
+                       float* cs, int32_t* flag, const int32_t* seq, int cache_rows, hipStream_t stream);
 hipError_t launch_ln_first(const uint16_t* x_in, const float* gamma, int B, int d, float eps,
                            float* xres, void* hq, float* hs, int nd, hipStream_t stream);
 hipError_t launch_epi_in(const float* part, SkqPlan pl, const float* scale, const float* cs,
-                         const int32_t* positions, int B, int H, int G, int dh, int F, int L_ctx,
+                         const int32_t* positions, const int32_t* seq, int cache_rows, int B, int H, int G,
+                         int dh, int F, int L_ctx,
                          float* q, void* kc_layer, void* vc_layer, void* actq, float* acts,
                          int blk_a, int nd, hipStream_t stream);
 hipError_t launch_residual(const float* part, SkqPlan pl, const float* scale, float* xres, int B,

@@ -18,10 +18,12 @@ namespace pd {
 
 __global__ __launch_bounds__(128) void prep_kernel(const int32_t* __restrict__ positions, int L_ctx,
                                                    int dh, double rope_base, float* __restrict__ cs,
-                                                   int32_t* __restrict__ flag) {
+                                                   int32_t* __restrict__ flag,
+                                                   const int32_t* __restrict__ seq, int cache_rows) {
     const int b = blockIdx.x, i = threadIdx.x;
     const int P = positions[b];
-    const bool bad = P < 0 || P >= L_ctx;
+    const int sb = seq ? seq[b] : b;  // cache row of this token row
+    const bool bad = P < 0 || P >= L_ctx || sb < 0 || sb >= cache_rows;
     // one flag word per row, rewritten every step (256 words; rows >= B cleared by block 0)
     if (i == 0) flag[b] = bad ? 1 : 0;
     if (b == 0)
@@ -106,7 +108,8 @@ __device__ __forceinline__ float sum_partials(const float* __restrict__ part, co
 // (32 gate, 32 up).  Cache element offsets follow the library block layouts.
 __global__ __launch_bounds__(256) void epi_in_kernel(
     const float* __restrict__ part, SkqPlan pl, const float* __restrict__ scale,
-    const float* __restrict__ cs, const int32_t* __restrict__ positions, int B, int H, int G, int dh, int F,
+    const float* __restrict__ cs, const int32_t* __restrict__ positions,
+    const int32_t* __restrict__ seq, int cache_rows, int B, int H, int G, int dh, int F,
     int L_ctx, int n_blocks_a, float* __restrict__ q, uint16_t* __restrict__ kc,
     uint16_t* __restrict__ vc, unsigned char* __restrict__ actq, float* __restrict__ acts,
     int blk_a, int nd) {
@@ -164,7 +167,8 @@ __global__ __launch_bounds__(256) void epi_in_kernel(
 
     const int item = blockIdx.x * 256 + threadIdx.x;
     const int P = positions[b];
-    const bool ok = P >= 0 && P < L_ctx;
+    const int sb = seq ? seq[b] : b;  // cache row this token row appends to
+    const bool ok = P >= 0 && P < L_ctx && sb >= 0 && sb < cache_rows;
     if (item < n_q + n_k) {
         // rotation pair (i, i + dh/2) of a q head or of k
         const bool is_k = item >= n_q;
@@ -180,7 +184,7 @@ __global__ __launch_bounds__(256) void epi_in_kernel(
             qrow[i] = rlo;
             qrow[i + half] = rhi;
         } else if (ok) {
-            const size_t blk = (((size_t)b * G + head) * (L_ctx >> 5) + (P >> 5)) * 32 * dh;
+            const size_t blk = (((size_t)sb * G + head) * (L_ctx >> 5) + (P >> 5)) * 32 * dh;
             const int tt = P & 31;
             int c = i;
             kc[blk + (((size_t)(c >> 4) * 2 + ((c & 15) >> 3)) * 32 + tt) * 8 + (c & 7)] = to_bf16(rlo);
@@ -193,7 +197,7 @@ __global__ __launch_bounds__(256) void epi_in_kernel(
         const int col = H * dh + G * dh + cv;
         float v = scale[col] * sum_partials(part, pl, stride, rowoff + col, col);
         if (ok) {
-            const size_t blk = (((size_t)b * G + head) * (L_ctx >> 5) + (P >> 5)) * 32 * dh;
+            const size_t blk = (((size_t)sb * G + head) * (L_ctx >> 5) + (P >> 5)) * 32 * dh;
             const int tt = P & 31;
             vc[blk + ((((size_t)(c >> 5) * 2 + (tt >> 4)) * 2 + ((tt & 7) >> 2)) * 32 + (c & 31)) * 8 +
                4 * ((tt & 15) >> 3) + (tt & 3)] = to_bf16(v);
@@ -427,8 +431,9 @@ __global__ __launch_bounds__(256) void vec_absmax_kernel(const float* __restrict
 }
 
 hipError_t launch_prep(const int32_t* positions, int B, int L_ctx, int dh, float rope_base,
-                       float* cs, int32_t* flag, hipStream_t stream) {
-    prep_kernel<<<dim3(B), dim3(128), 0, stream>>>(positions, L_ctx, dh, (double)rope_base, cs, flag);
+                       float* cs, int32_t* flag, const int32_t* seq, int cache_rows, hipStream_t stream) {
+    prep_kernel<<<dim3(B), dim3(128), 0, stream>>>(positions, L_ctx, dh, (double)rope_base, cs, flag, seq,
+                                                   cache_rows);
     return hipGetLastError();
 }
 
@@ -440,7 +445,8 @@ hipError_t launch_ln_first(const uint16_t* x_in, const float* gamma, int B, int 
 }
 
 hipError_t launch_epi_in(const float* part, SkqPlan pl, const float* scale, const float* cs,
-                         const int32_t* positions, int B, int H, int G, int dh, int F, int L_ctx,
+                         const int32_t* positions, const int32_t* seq, int cache_rows, int B, int H, int G,
+                         int dh, int F, int L_ctx,
                          float* q, void* kc_layer, void* vc_layer, void* actq, float* acts,
                          int blk_a, int nd, hipStream_t stream) {
     if (blk_a < 1 || blk_a > 64) return hipErrorInvalidValue;
@@ -448,7 +454,7 @@ hipError_t launch_epi_in(const float* part, SkqPlan pl, const float* scale, cons
     const int n_blocks_a = (items + 255) / 256;
     const int n_blocks_b = (F / 128 + blk_a - 1) / blk_a;
     epi_in_kernel<<<dim3(n_blocks_a + n_blocks_b, B), dim3(256), 0, stream>>>(
-        part, pl, scale, cs, positions, B, H, G, dh, F, L_ctx, n_blocks_a, q,
+        part, pl, scale, cs, positions, seq, cache_rows, B, H, G, dh, F, L_ctx, n_blocks_a, q,
         reinterpret_cast<uint16_t*>(kc_layer), reinterpret_cast<uint16_t*>(vc_layer),
         reinterpret_cast<unsigned char*>(actq), acts, blk_a, nd);
     return hipGetLastError();

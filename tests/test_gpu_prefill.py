@@ -1,0 +1,126 @@
+"""GPU parity of prefill / incremental prefill (Section 2.2, Section 3.5): many tokens per
+sequence in one call, causal attention through the cache, against the fp64 oracle applied
+to the same token rows in position order."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from workloads import synth
+from workloads.configs import Workload
+
+pytestmark = pytest.mark.gpu
+MAX_SCALED, REL_L2 = 2e-2, 5e-3
+
+
+@pytest.fixture(scope="module")
+def pd():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2211_05102_amd as m
+    m.lib()
+    return m
+
+
+def bits_np(t):
+    return t.detach().cpu().contiguous().view(torch.int16).numpy().view(np.uint16).copy()
+
+
+def widen(b):
+    return (b.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+
+
+@pytest.mark.parametrize("case", [
+    # (layers, d, H, G, dh, F, cache rows, L_ctx, tokens already cached per sequence, new tokens per sequence)
+    (2, 256, 4, 1, 64, 512, 3, 128, [0, 0, 0], [40, 7, 1]),          # whole prefill, ragged lengths
+    (2, 384, 6, 1, 128, 384, 2, 352, [17, 64], [300, 150]),          # incremental, several 256-row chunks
+    (1, 512, 4, 4, 128, 256, 2, 96, [5, 0], [33, 64]),               # multihead K/V
+])
+def test_prefill_vs_oracle(pd, case):
+    from paper_2211_05102_amd import binding
+    L_, d, H, G, dh, F, S, L, cached, new = case
+    w = Workload("prefill", L_, d, H, dh, F, S, L, n_kv_heads=G)
+    dec = pd.Decoder(w)
+    desc_o = oracle.make_desc(w)
+    # token rows, interleaved round-robin over the sequences, each sequence in position order
+    rows = []
+    for i in range(max(new)):
+        for s in range(S):
+            if i < new[s]:
+                rows.append((s, cached[s] + i))
+    seq = np.array([r[0] for r in rows], dtype=np.int32)
+    pos = np.array([r[1] for r in rows], dtype=np.int32)
+    N = len(rows)
+    g = torch.Generator(device="cuda").manual_seed(7)
+    x = torch.randn(N, d, generator=g, device="cuda").to(torch.bfloat16)
+
+    layer_bytes = binding.packed_layer_bytes(dec.desc)
+    packed = torch.empty(L_ * layer_bytes, dtype=torch.uint8, device="cuda")
+    kvb = binding.kv_cache_bytes(dec.desc, S, L)
+    kc = torch.empty(kvb // 2, dtype=torch.bfloat16, device="cuda")
+    vc = torch.empty_like(kc)
+    live = torch.arange(L, device="cuda")[None, :] < torch.tensor(cached, device="cuda")[:, None]
+    lv = live[:, :, None] if G == 1 else live[:, None, :, None]
+    x64 = oracle.bf16_bits_to_f64_fast(bits_np(x))
+    k_after, k_before = [], []
+    for l in range(L_):
+        wts = synth.layer_weights(w, l, "cuda")
+        dec.pack_layer(wts, packed[l * layer_bytes:(l + 1) * layer_bytes])
+        k, v = synth.kv_layer(w, l, "cuda")
+        k = torch.where(lv, k, torch.full_like(k, float("nan")))  # nothing beyond the cached prefix may be read
+        v = torch.where(lv, v, torch.full_like(v, float("inf")))
+        dec.kv_import(k, kc, l, False)
+        dec.kv_import(v, vc, l, True)
+        kb, vb = bits_np(k), bits_np(v)
+        k_before.append((kb.copy(), vb.copy()))
+        oracle.decode_layer(desc_o, {n: t.cpu() for n, t in wts.items()}, kb, vb, pos, x64, L, cache_row=seq)
+        k_after.append((kb, vb))
+    ws = torch.empty(binding.workspace_bytes(dec.desc, min(N, 256), L), dtype=torch.uint8, device="cuda")
+    ws.fill_(0xFF)
+    out = torch.full((N, d), float("nan"), dtype=torch.bfloat16, device="cuda")
+    dec.prefill(packed, kc, vc, x, torch.from_numpy(seq).cuda(), torch.from_numpy(pos).cuda(), S, L, out, ws)
+    dec.check_async(ws)
+    got = widen(bits_np(out))
+    want = widen(oracle.f64_to_bf16_bits(x64))
+    assert np.all(np.isfinite(got))
+    scaled = float(np.max(np.abs(got - want) / np.maximum(1.0, np.abs(want))))
+    rel = float(np.linalg.norm(got - want) / np.linalg.norm(want))
+    print(f"[prefill] {case}: {N} token rows, scaled-max {scaled:.3e} rel-L2 {rel:.3e}", flush=True)
+    assert scaled <= MAX_SCALED and rel <= REL_L2
+    # cache: exactly the slots [cached, cached + new) of every sequence (and K/V head) changed,
+    # and they hold the oracle's values to a bf16 step
+    t = np.arange(L)[None, :]
+    want_changed = (t >= np.array(cached)[:, None]) & (t < (np.array(cached) + np.array(new))[:, None])
+    shape = (S, L, dh) if G == 1 else (S, G, L, dh)
+    for l in range(L_):
+        kg = torch.empty(*shape, dtype=torch.bfloat16, device="cuda")
+        vg = torch.empty_like(kg)
+        dec.kv_export(kc, kg, l, False)
+        dec.kv_export(vc, vg, l, True)
+        for got_c, (before, after) in ((bits_np(kg), (k_before[l][0], k_after[l][0])),
+                                        (bits_np(vg), (k_before[l][1], k_after[l][1]))):
+            changed = (got_c != before).any(axis=-1)
+            wc = want_changed if G == 1 else np.broadcast_to(want_changed[:, None, :], changed.shape)
+            assert np.array_equal(changed, wc), l
+            a, b = widen(got_c[changed]), widen(after[changed])
+            assert np.max(np.abs(a - b) / np.maximum(1.0, np.abs(b))) <= MAX_SCALED
+
+
+def test_prefill_flags_bad_sequence_ids(pd):
+    from paper_2211_05102_amd import binding
+    w = Workload("pfbad", 1, 256, 4, 64, 256, 2, 64)
+    dec = pd.Decoder(w)
+    packed = torch.empty(binding.packed_layer_bytes(dec.desc), dtype=torch.uint8, device="cuda")
+    dec.pack_layer(synth.layer_weights(w, 0, "cuda"), packed)
+    kc = torch.zeros(binding.kv_cache_bytes(dec.desc, 2, 64) // 2, dtype=torch.bfloat16, device="cuda")
+    vc = torch.zeros_like(kc)
+    k0 = kc.clone()
+    x = torch.randn(3, 256, device="cuda").to(torch.bfloat16)
+    ws = torch.empty(binding.workspace_bytes(dec.desc, 3, 64), dtype=torch.uint8, device="cuda")
+    out = torch.empty_like(x)
+    seq = torch.tensor([0, 2, 1], dtype=torch.int32, device="cuda")  # 2 is not a cache row
+    dec.prefill(packed, kc, vc, x, seq, torch.zeros(3, dtype=torch.int32, device="cuda"), 2, 64, out, ws)
+    with pytest.raises(pd.PdError) as e:
+        dec.check_async(ws)
+    assert e.value.code == binding.PD_ERR_POSITION
+    assert not torch.equal(kc.view(torch.int16), k0.view(torch.int16))  # rows 0 and 1 did append

@@ -617,3 +617,26 @@ def test_multihead_byte_model_scales_kv_by_heads():
     w = Workload("t", 4, 256, 8, 64, 512, 2, 128)
     assert C.kv_read_bytes(w.with_(n_kv_heads=8), [127, 63]) == 8 * C.kv_read_bytes(w, [127, 63])
     assert w.with_(n_kv_heads=8).n_in == w.n_in + 2 * 7 * 64
+
+
+# ------------------------------------------------------ prefill (Section 2.2) ---
+
+def test_token_rows_sharing_a_cache_row_are_a_causal_forward_pass():
+    # the decode layer applied to T token rows of one sequence (all mapped to cache row 0, in
+    # position order) is the prefill of those tokens: it must equal the separately written
+    # causal [T x T] layer, token by token
+    w = Workload("pf", 1, 64, 2, 16, 32, 1, 16)
+    wts = synth.layer_weights(w, 0, "cpu")
+    desc = oracle.make_desc(w)
+    rng = np.random.default_rng(31)
+    T = 11
+    x = rng.standard_normal((T, w.d_model))
+    a = x.copy()
+    oracle.causal_layer(desc, wts, a)
+    b = x.copy()
+    kc = np.full((1, w.l_ctx, w.d_head), 0x7fc0, dtype=np.uint16)  # NaN everywhere: only appended slots may be read
+    vc = kc.copy()
+    oracle.decode_layer(desc, wts, kc, vc, np.arange(T, dtype=np.int32), b, w.l_ctx,
+                        cache_row=np.zeros(T, dtype=np.int32))
+    assert np.all(np.isfinite(b))
+    assert np.max(np.abs(a - b)) <= 1e-12 * np.max(np.abs(a))
