@@ -14,6 +14,8 @@ Prints ONE JSON line.
   per_config           every named workload: ms/step (median, min), tokens/s, algorithmic GB/s,
                        fraction of the HBM peak, int8 matrix-pipe utilisation, two-phase bound
   generate             the generation loop (64 steps, sampling head included): ms per token
+  prefill              2048 input tokens of one sequence through the same stack (Section 2.2)
+  variants             multiquery vs multihead twin of the 62B-shaped stack (Section 4.2)
   copy_ceiling         a plain device-to-device copy, the practical bandwidth ceiling
   cpu_baseline         the fp64 oracle on a bounded sample of the headline workload
 """
@@ -33,6 +35,11 @@ HBM_PEAK_GBPS = 8000.0     # MI355X HBM3E, published
 INT8_PEAK_OPS = 5.0e15     # dense int8 MFMA, published
 BF16_PEAK_FLOPS = 2.5e15   # dense bf16 MFMA, published
 ACT_PLANES = 3             # int8 digit planes per activation (the library's default)
+
+
+def note(msg):
+    """Progress line on stderr before each GPU phase (names the phase if the run dies in it)."""
+    print(f"[bench] {msg}", file=sys.stderr, flush=True)
 
 
 def cpu_baseline(w, stack_rows=4, seconds_budget=20.0):
@@ -124,9 +131,11 @@ def time_workload(w, steps, warmup, eager_steps=0):
     import torch
     from paper_2211_05102_amd import harness
     t0 = time.perf_counter()
+    note(f"{w.name}: building the stack on the device")
     st = harness.DeviceStack(w)
     torch.cuda.synchronize()
     setup = time.perf_counter() - t0
+    note(f"{w.name}: graph capture and {steps} timed replays" + (f", {eager_steps} eager" if eager_steps else ""))
     positions = st.positions.cpu().tolist()
     stream = torch.cuda.Stream()
     with torch.cuda.stream(stream):
@@ -156,11 +165,13 @@ def time_generate(w, n_steps, vocab, top_k, top_p, temperature):
     from paper_2211_05102_amd import harness
     start = w.l_ctx - n_steps
     wg = w.with_(positions="ragged", pos_lo=start, pos_hi=start + 1, name=f"{w.name}[generate]")
+    note(f"{wg.name}: building the stack and the sampling head (vocab {vocab})")
     st = harness.GenerateStack(wg, vocab, n_steps)
     stream = torch.cuda.Stream()
     out = {}
     with torch.cuda.stream(stream):
         for use_graph in (True, False):
+            note(f"{wg.name}: {n_steps} steps, {'graph replay' if use_graph else 'eager'}")
             st.positions.fill_(start)
             torch.cuda.synchronize()
             t0 = time.perf_counter()
@@ -176,6 +187,53 @@ def time_generate(w, n_steps, vocab, top_k, top_p, temperature):
             "kv_len_start": start, "ms_per_token_graph": out["graph"], "ms_per_token_eager": out["eager"],
             "tokens_per_s": wg.batch / (out["graph"] * 1e-3),
             "distinct_tokens_drawn": int(tok.unique().numel())}
+
+
+def time_prefill(w, n_seqs, tokens_per_seq):
+    """Prefill of n_seqs sequences of tokens_per_seq tokens each (Section 2.2) on the layer stack of
+    workload `w`, empty caches: tokens per second and model-flops utilisation against the bf16 peak."""
+    import torch
+    from workloads import configs as C
+    from workloads import synth
+    from paper_2211_05102_amd import binding
+    wp = w.with_(batch=n_seqs, l_ctx=tokens_per_seq, name=f"{w.name}[prefill]")
+    note(f"{wp.name}: packing the stack, {n_seqs} x {tokens_per_seq} tokens")
+    dec = binding.Decoder(wp)
+    lb = binding.packed_layer_bytes(dec.desc)
+    packed = torch.empty(wp.n_layers * lb, dtype=torch.uint8, device="cuda")
+    for l in range(wp.n_layers):
+        dec.pack_layer(synth.layer_weights(wp, l, "cuda"), packed[l * lb:(l + 1) * lb])
+    kvb = binding.kv_cache_bytes(dec.desc, n_seqs, tokens_per_seq)
+    kc = torch.zeros(kvb // 2, dtype=torch.bfloat16, device="cuda")
+    vc = torch.zeros_like(kc)
+    n = n_seqs * tokens_per_seq
+    pos = torch.arange(tokens_per_seq, dtype=torch.int32, device="cuda").repeat_interleave(n_seqs).contiguous()
+    seq = torch.arange(n_seqs, dtype=torch.int32, device="cuda").repeat(tokens_per_seq).contiguous()
+    g = torch.Generator(device="cuda").manual_seed(3)
+    x = torch.randn(n, wp.d_model, generator=g, device="cuda").to(torch.bfloat16)
+    out = torch.empty_like(x)
+    ws = torch.empty(binding.workspace_bytes(dec.desc, min(n, 256), tokens_per_seq), dtype=torch.uint8, device="cuda")
+    # Everything above was enqueued on the default stream; the timed work runs on another one.  Without
+    # this wait the prefill would start while weight generation is still running -- in memory the
+    # allocator has already handed on to `ws`, whose tables the kernels take loop bounds from.
+    torch.cuda.synchronize()
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        note(f"{wp.name}: prefill warm-up, then 2 timed")
+        dec.prefill(packed, kc, vc, x, seq, pos, n_seqs, tokens_per_seq, out, ws, stream)  # warm-up
+        torch.cuda.synchronize()
+        ms = event_times(lambda: dec.prefill(packed, kc, vc, x, seq, pos, n_seqs, tokens_per_seq, out, ws, stream),
+                         2, stream)
+        dec.check_async(ws, stream)
+    s = min(ms) * 1e-3
+    flops = 2.0 * C.weight_bytes(wp) * n + 4.0 * wp.n_layers * wp.n_heads * wp.d_head * n_seqs * (
+        tokens_per_seq * (tokens_per_seq + 1) / 2)
+    del packed, kc, vc, x, out, ws
+    torch.cuda.empty_cache()
+    return {"sequences": n_seqs, "tokens_per_sequence": tokens_per_seq, "ms": s * 1e3, "tokens_per_s": n / s,
+            "model_flops": flops, "mfu_vs_bf16_peak": flops / s / BF16_PEAK_FLOPS,
+            "int8_mfma_util": 2.0 * C.weight_bytes(wp) * n * ACT_PLANES / s / INT8_PEAK_OPS,
+            "note": "chunks of 256 token rows, each streaming the stack once; attention re-reads the prefix per token"}
 
 
 def copy_ceiling():
@@ -201,6 +259,8 @@ def main():
     ap.add_argument("--layers", type=int, default=0,
                     help="run a shorter stack of the same layer shape (kernel tuning; not the headline workload)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-graph", action="store_true",
+                    help="eager launches only (counter passes under rocprofv3)")
     ap.add_argument("--headline-only", action="store_true",
                     help="skip per_config, generate and copy_ceiling (profiling runs)")
     ap.add_argument("--gemm-wg-in", type=int, default=0)
@@ -216,7 +276,7 @@ def main():
         sys.exit(2)
 
     import torch
-    from workloads import WORKLOADS
+    from workloads import WORKLOADS, VARIANTS
     from workloads import configs as C
     from paper_2211_05102_amd import harness
 
@@ -224,6 +284,7 @@ def main():
     if args.layers:
         w = w.with_(n_layers=args.layers, name=f"{w.name}[{args.layers} layers]")
     t_setup = time.perf_counter()
+    note(f"{w.name}: building the stack on the device")
     st = harness.DeviceStack(w)
     for name, val in (("gemm_workgroups_in", args.gemm_wg_in), ("gemm_workgroups_out", args.gemm_wg_out),
                       ("attn_blocks_per_split", args.attn_bps)):
@@ -244,22 +305,28 @@ def main():
         torch.cuda.synchronize()
         del src, dst
     with torch.cuda.stream(stream):
-        st.dec.graph_capture(st.packed, st.k_cache, st.v_cache, st.x_in, st.positions, w.l_ctx,
-                             st.x_out, st.workspace, stream)
+        use_graph = not args.no_graph
+        note(f"{w.name}: {'graph capture, ' if use_graph else 'eager, '}warm-up, {args.steps} timed steps")
+        if use_graph:
+            st.dec.graph_capture(st.packed, st.k_cache, st.v_cache, st.x_in, st.positions, w.l_ctx,
+                                 st.x_out, st.workspace, stream)
+        one_step = (lambda: st.dec.graph_replay(stream)) if use_graph else (lambda: st.step(stream))
         for _ in range(args.warmup):
-            st.dec.graph_replay(stream)
+            one_step()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for _ in range(args.steps):
-            st.dec.graph_replay(stream)
+            one_step()
         torch.cuda.synchronize()
         elapsed = time.perf_counter() - t0
         st.dec.check_async(st.workspace, stream)
         # per-step events: graph replay, then eager launches
-        t_graph = event_times(lambda: st.dec.graph_replay(stream), args.steps, stream)
+        note(f"{w.name}: per-step events, graph and eager")
+        t_graph = event_times(one_step, args.steps, stream)
         t_eager = event_times(lambda: st.step(stream), max(3, args.steps // 2), stream)
 
         # second pass: the same K steps, eager launches, events around the dominant kernel
+        note(f"{w.name}: eager passes with events around each kernel class")
         st.dec.set_option("profile_kernel", 1)
         for _ in range(args.steps):
             st.step(stream)
@@ -306,7 +373,7 @@ def main():
         "config": {"workload": w.name, "n_layers": w.n_layers, "d_model": w.d_model,
                    "n_heads": w.n_heads, "d_head": w.d_head, "d_ff": w.d_ff, "batch": w.batch,
                    "kv_len": w.l_ctx, "positions": w.positions, "weights": "int8 per-channel",
-                   "launch": "hipGraph replay", "setup_s": round(t_setup, 1)},
+                   "launch": "eager" if args.no_graph else "hipGraph replay", "setup_s": round(t_setup, 1)},
         "timing": {"graph_ms_median": statistics.median(t_graph), "graph_ms_min": min(t_graph),
                    "eager_ms_median": statistics.median(t_eager), "eager_ms_min": min(t_eager),
                    "clock": "HIP events on the launch stream, one pair per step"},
@@ -318,11 +385,13 @@ def main():
                      "bytes_per_launch": k_bytes, "avg_launch_us": k_avg_s * 1e6},
         "kernels": per_kernel,
     }
-    del st
+    del st, one_step  # (the closure holds the stack)
     torch.cuda.empty_cache()
     if not args.headline_only:
+        note("copy ceiling")
         out["copy_ceiling"] = copy_ceiling()
         out["generate"] = time_generate(w, 64, 256000, 40, 0.9, 1.0)
+        out["prefill"] = time_prefill(w, 1, 2048)
         mine = summarize(w, positions, statistics.median(t_graph))
         mine.update({"ms_min": min(t_graph), "steps": args.steps, "launch": "hipGraph replay",
                      "eager_ms_median": statistics.median(t_eager), "eager_ms_min": min(t_eager)})
@@ -330,7 +399,10 @@ def main():
         for name, k, e in (("c1_tiny", 50, 20), ("c2_8b", 30, 10), ("c4_540b_shard8", 10, 4), ("c5_62b_long", 6, 0)):
             if name != args.workload:
                 out["per_config"][name] = time_workload(WORKLOADS[name], steps=k, warmup=2, eager_steps=e)
+        # Section 4.2: the same stack with one K/V head per query head reads H/2 times the KV bytes
+        out["variants"] = {name: time_workload(v, steps=5, warmup=2) for name, v in VARIANTS.items()}
     if not args.no_cpu_baseline:
+        note("cpu baseline (oracle on host cores)")
         out["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(out))
 

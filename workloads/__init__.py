@@ -1,2 +1,2 @@
 """Workload shapes (configs) and seeded synthetic input generators (synth)."""
-from .configs import WORKLOADS, Workload, MASTER_SEED  # noqa: F401
+from .configs import WORKLOADS, VARIANTS, Workload, MASTER_SEED  # noqa: F401

@@ -66,6 +66,14 @@ WORKLOADS: Dict[str, Workload] = {
                             positions="ragged", pos_lo=4096, pos_hi=8192),
 }
 
+# Variants for the comparisons of Section 4.2 / Section 4.4 (not BASELINE workloads): the
+# multihead twin of the 62B-shaped stack (one K/V head per query head, d_head 128 as in the
+# paper's multihead variant) and the multiquery stack at the batch that twin fits at.
+VARIANTS: Dict[str, Workload] = {
+    "c3_62b_b32": Workload("c3_62b_b32", 64, 8192, 32, 256, 32768, 32, 2048),
+    "c3_62b_b32_multihead": Workload("c3_62b_b32_multihead", 64, 8192, 64, 128, 32768, 32, 2048, n_kv_heads=64),
+}
+
 
 def weight_bytes_per_layer(w: Workload) -> int:
     """int8 bytes of the two fused projection matrices of one layer."""
