@@ -48,6 +48,7 @@ def lib():
         _lib.orc_f64_to_bf16.argtypes = [ctypes.c_double]
         _lib.orc_num_threads.restype = ctypes.c_int
         _lib.orc_decode_layer.restype = ctypes.c_int
+        _lib.orc_decode_layer_w16.restype = ctypes.c_int
         _lib.orc_sample_topk_topp.restype = ctypes.c_int
         _lib.orc_causal_layer.restype = ctypes.c_int
     return _lib
@@ -101,6 +102,18 @@ def qmatmul(a: np.ndarray, q8: np.ndarray, scale_bits: np.ndarray) -> np.ndarray
     out = np.empty((R, N), dtype=np.float64)
     lib().orc_qmatmul(_p(a, np.float64), _p(q8, np.int8), _p(scale_bits, np.uint16),
                       ctypes.c_int32(R), ctypes.c_int32(K), ctypes.c_int32(N), _p(out, np.float64))
+    return out
+
+
+def wmatmul_bf16(a: np.ndarray, w_bits: np.ndarray) -> np.ndarray:
+    """a [R, K] fp64 times bf16 weights [K, N] (bit patterns), no scales."""
+    a = np.ascontiguousarray(a, dtype=np.float64)
+    w = _bits(w_bits)
+    R, K = a.shape
+    assert w.shape[0] == K
+    out = np.empty((R, w.shape[1]), dtype=np.float64)
+    lib().orc_wmatmul_bf16(_p(a, np.float64), _p(w, np.uint16), ctypes.c_int32(R), ctypes.c_int32(K),
+                           ctypes.c_int32(w.shape[1]), _p(out, np.float64))
     return out
 
 
@@ -207,10 +220,22 @@ def decode_layer(desc: _Desc, weights: dict, kc: np.ndarray, vc: np.ndarray,
     tail = (l_ctx, desc.d_head) if G == 1 else (G, l_ctx, desc.d_head)
     assert kc.shape[1:] == tail and vc.shape == kc.shape, (kc.shape, tail)
     assert rows.max() < kc.shape[0]
-    w_in, w_out = _i8(weights["w_in"]), _i8(weights["w_out"])
-    s_in, s_out, gamma = _bits(weights["s_in"]), _bits(weights["s_out"]), _bits(weights["gamma"])
     n_in = desc.n_heads * desc.d_head + 2 * G * desc.d_head + 2 * desc.d_ff
     k_out = desc.n_heads * desc.d_head + desc.d_ff
+    gamma = _bits(weights["gamma"])
+    if "s_in" not in weights:  # bf16 weights, no scales (Section 4.4 baseline)
+        w_in, w_out = _bits(weights["w_in"]), _bits(weights["w_out"])
+        assert w_in.shape == (desc.d_model, n_in) and w_out.shape == (k_out, desc.d_model)
+        rc = lib().orc_decode_layer_w16(ctypes.byref(desc), _p(w_in, np.uint16), _p(w_out, np.uint16),
+                                        _p(gamma, np.uint16), _p(kc, np.uint16), _p(vc, np.uint16),
+                                        _p(rows, np.int32), _p(pos, np.int32), ctypes.c_int32(R),
+                                        ctypes.c_int32(l_ctx), _p(x, np.float64),
+                                        ctypes.c_int32(1 if add_residual else 0))
+        if rc != 0:
+            raise ValueError("oracle decode_layer (bf16 weights): bad argument")
+        return
+    w_in, w_out = _i8(weights["w_in"]), _i8(weights["w_out"])
+    s_in, s_out = _bits(weights["s_in"]), _bits(weights["s_out"])
     assert w_in.shape == (desc.d_model, n_in) and w_out.shape == (k_out, desc.d_model)
     rc = lib().orc_decode_layer(ctypes.byref(desc), _p(w_in, np.int8), _p(s_in, np.uint16),
                                 _p(w_out, np.int8), _p(s_out, np.uint16), _p(gamma, np.uint16),

@@ -128,6 +128,26 @@ void orc_qmatmul(const double* a, const int8_t* q8, const uint16_t* scale,
     }
 }
 
+/* out[r][n] = sum_k a[r][k] * w[k][n] with the weights stored in bf16 and no
+ * scales: the unquantised baseline the int8 weights are compared with
+ * (Section 3.6, Section 4.4).  w: [K][N] row-major bf16 bits. */
+void orc_wmatmul_bf16(const double* a, const uint16_t* w, int32_t R, int32_t K, int32_t N, double* out) {
+#pragma omp parallel for schedule(static)
+    for (int32_t n = 0; n < N; n++)
+        for (int32_t r = 0; r < R; r++) {
+            double acc = 0.0;
+            for (int32_t k = 0; k < K; k++) acc += a[(size_t)r * K + k] * orc_bf16_to_f64(w[(size_t)k * N + n]);
+            out[(size_t)r * N + n] = acc;
+        }
+}
+
+/* the projection of a layer in either weight format */
+static void orc_project(const double* a, const void* w, const uint16_t* scale, int32_t w16,
+                        int32_t R, int32_t K, int32_t N, double* out) {
+    if (w16) orc_wmatmul_bf16(a, (const uint16_t*)w, R, K, N, out);
+    else orc_qmatmul(a, (const int8_t*)w, scale, R, K, N, out);
+}
+
 /* ------------------------------------------------------------------ RoPE --- */
 
 /* Rotate y[0..dh) in place by the angles pos * base^(-2i/dh), pairing element
@@ -229,11 +249,11 @@ void orc_swiglu(const double* g, const double* u, int32_t F, double* a) {
  *      contribution (a shard's unreduced partial) instead of x + contribution.
  * Returns 0, or -1 on a bad argument.
  */
-int orc_decode_layer(const orc_desc* m, const int8_t* w_in, const uint16_t* s_in,
-                     const int8_t* w_out, const uint16_t* s_out, const uint16_t* gamma,
-                     uint16_t* kc, uint16_t* vc, const int32_t* cache_row,
-                     const int32_t* positions, int32_t R, int32_t L_ctx,
-                     double* x, int32_t add_residual) {
+static int orc_decode_layer_impl(const orc_desc* m, int32_t w16, const void* w_in, const uint16_t* s_in,
+                                 const void* w_out, const uint16_t* s_out, const uint16_t* gamma,
+                                 uint16_t* kc, uint16_t* vc, const int32_t* cache_row,
+                                 const int32_t* positions, int32_t R, int32_t L_ctx,
+                                 double* x, int32_t add_residual) {
     int32_t d = m->d_model, H = m->n_heads, dh = m->d_head, F = m->d_ff;
     /* K/V heads: 1 = multiquery (Section 3.3), H = multihead (every query head has its
      * own K/V head).  With G heads the columns of w_in are q(H*dh) | k(G*dh) | v(G*dh) |
@@ -253,7 +273,7 @@ int orc_decode_layer(const orc_desc* m, const int8_t* w_in, const uint16_t* s_in
     for (int32_t r = 0; r < R; r++)
         orc_layernorm(x + (size_t)r * d, gamma, d, m->ln_eps, h + (size_t)r * d);
 
-    orc_qmatmul(h, w_in, s_in, R, d, n_in, z);
+    orc_project(h, w_in, s_in, w16, R, d, n_in, z);
 
     for (int32_t r = 0; r < R; r++) {
         double* zr = z + (size_t)r * n_in;
@@ -280,12 +300,31 @@ int orc_decode_layer(const orc_desc* m, const int8_t* w_in, const uint16_t* s_in
         orc_swiglu(g, u, F, oar + (size_t)H * dh);
     }
 
-    orc_qmatmul(oa, w_out, s_out, R, k_out, d, y);
+    orc_project(oa, w_out, s_out, w16, R, k_out, d, y);
 
     for (size_t i = 0; i < (size_t)R * d; i++) x[i] = add_residual ? x[i] + y[i] : y[i];
 
     free(h); free(z); free(oa); free(y);
     return 0;
+}
+
+int orc_decode_layer(const orc_desc* m, const int8_t* w_in, const uint16_t* s_in,
+                     const int8_t* w_out, const uint16_t* s_out, const uint16_t* gamma,
+                     uint16_t* kc, uint16_t* vc, const int32_t* cache_row,
+                     const int32_t* positions, int32_t R, int32_t L_ctx,
+                     double* x, int32_t add_residual) {
+    return orc_decode_layer_impl(m, 0, w_in, s_in, w_out, s_out, gamma, kc, vc, cache_row, positions, R,
+                                 L_ctx, x, add_residual);
+}
+
+/* The same layer with both matrices stored in bf16, no scales (the bf16-weight
+ * baseline of Section 4.4). */
+int orc_decode_layer_w16(const orc_desc* m, const uint16_t* w_in, const uint16_t* w_out,
+                         const uint16_t* gamma, uint16_t* kc, uint16_t* vc, const int32_t* cache_row,
+                         const int32_t* positions, int32_t R, int32_t L_ctx, double* x,
+                         int32_t add_residual) {
+    return orc_decode_layer_impl(m, 1, w_in, NULL, w_out, NULL, gamma, kc, vc, cache_row, positions, R,
+                                 L_ctx, x, add_residual);
 }
 
 /* --------------------------------------------------- sampling head (f1) --- */

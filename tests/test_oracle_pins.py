@@ -640,3 +640,52 @@ def test_token_rows_sharing_a_cache_row_are_a_causal_forward_pass():
                         cache_row=np.zeros(T, dtype=np.int32))
     assert np.all(np.isfinite(b))
     assert np.max(np.abs(a - b)) <= 1e-12 * np.max(np.abs(a))
+
+
+# ------------------------------------------- bf16 weights (Section 4.4 baseline) ---
+
+def test_wmatmul_bf16_vs_numpy_matmul_and_orientation():
+    a = RNG.standard_normal((5, 96))
+    w = rand_bf16(96, 40, scale=0.05)
+    got = oracle.wmatmul_bf16(a, w)
+    want = a @ widen(w)
+    assert np.max(np.abs(got - want)) <= 1e-13 * np.max(np.abs(want))
+    # a one-hot row of `a` picks a row of w, never a column
+    e = np.zeros((1, 96)); e[0, 17] = 1.0
+    assert np.array_equal(oracle.wmatmul_bf16(e, w)[0], widen(w)[17])
+
+
+def test_bf16_weight_layer_equals_int8_layer_when_the_weights_coincide():
+    # int8 values times a power-of-two scale are exact in bf16 (|q| <= 127 fits the 8-bit
+    # significand): the layer with bf16 weights q * 2^-e must equal the int8 layer with scales
+    # 2^-e, whatever the wiring between the two projections is
+    w = Workload("w16", 1, 128, 2, 64, 256, 3, 64)
+    wts = synth.layer_weights(w, 0, "cpu")
+    e_in = torch.from_numpy(RNG.integers(6, 10, w.n_in)).float()
+    e_out = torch.from_numpy(RNG.integers(6, 10, w.d_model)).float()
+    wts["s_in"] = torch.pow(2.0, -e_in).to(torch.bfloat16)
+    wts["s_out"] = torch.pow(2.0, -e_out).to(torch.bfloat16)
+    w16 = {"w_in": (wts["w_in"].float() * wts["s_in"].float()).to(torch.bfloat16),
+           "w_out": (wts["w_out"].float() * wts["s_out"].float()).to(torch.bfloat16),
+           "gamma": wts["gamma"]}
+    assert torch.equal(w16["w_in"].float(), wts["w_in"].float() * wts["s_in"].float())  # exact
+    desc = oracle.make_desc(w)
+    kc, vc = (bits_of(t) for t in synth.kv_layer(w, 0, "cpu"))
+    pos = np.array([5, 63, 0], dtype=np.int32)
+    x = RNG.standard_normal((3, w.d_model))
+    xa, ka, va = x.copy(), kc.copy(), vc.copy()
+    oracle.decode_layer(desc, wts, ka, va, pos, xa, w.l_ctx)
+    xb, kb, vb = x.copy(), kc.copy(), vc.copy()
+    oracle.decode_layer(desc, w16, kb, vb, pos, xb, w.l_ctx)
+    assert np.max(np.abs(xa - xb)) <= 1e-12 * np.max(np.abs(xa))
+    assert np.array_equal(ka, kb) and np.array_equal(va, vb)
+
+
+def test_bf16_weight_workload_streams_and_byte_model():
+    from workloads import configs as C
+    w8 = Workload("t", 2, 128, 2, 64, 256, 2, 64)
+    w16 = w8.with_(weights="bf16")
+    a, b = synth.layer_weights(w16, 1, "cpu"), synth.layer_weights(w16, 1, "cpu")
+    assert set(a) == {"w_in", "w_out", "gamma"} and a["w_in"].dtype == torch.bfloat16
+    assert torch.equal(a["w_in"], b["w_in"]) and torch.equal(a["gamma"], synth.layer_weights(w8, 1, "cpu")["gamma"])
+    assert C.weight_bytes(w16) == 2 * C.weight_bytes(w8)

@@ -35,6 +35,9 @@ class Workload:
     rope_base: float = 10000.0
     ln_eps: float = 1e-6
     n_kv_heads: int = 1
+    # storage of the two projection matrices: "int8" (with per-channel bf16 scales,
+    # Section 3.6) or "bf16" (no scales: the baseline of Section 4.4)
+    weights: str = "int8"
 
     @property
     def n_in(self) -> int:
@@ -72,12 +75,15 @@ WORKLOADS: Dict[str, Workload] = {
 VARIANTS: Dict[str, Workload] = {
     "c3_62b_b32": Workload("c3_62b_b32", 64, 8192, 32, 256, 32768, 32, 2048),
     "c3_62b_b32_multihead": Workload("c3_62b_b32_multihead", 64, 8192, 64, 128, 32768, 32, 2048, n_kv_heads=64),
+    # the 62B-shaped stack with bf16 weights (Section 4.4 compares the two weight formats)
+    "c3_62b_bf16w": Workload("c3_62b_bf16w", 64, 8192, 32, 256, 32768, 64, 2048, weights="bf16"),
 }
 
 
 def weight_bytes_per_layer(w: Workload) -> int:
-    """int8 bytes of the two fused projection matrices of one layer."""
-    return w.d_model * w.n_in + w.k_out * w.d_model
+    """Bytes of the two fused projection matrices of one layer (one per int8 weight, two per
+    bf16 weight)."""
+    return (w.d_model * w.n_in + w.k_out * w.d_model) * (2 if w.weights == "bf16" else 1)
 
 
 def weight_bytes(w: Workload) -> int:

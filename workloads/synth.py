@@ -58,19 +58,27 @@ def layer_weights(w: Workload, layer: int, device="cpu", sigma: float = 0.02,
     w_out [k_out, d_model] int8, rows ordered attention-out | FFN activation
     s_out [d_model]        bf16
     gamma [d_model]        bf16, 1 + N(0, 0.02) so a mis-indexed gain is visible
+
+    A workload with weights == "bf16" gets the same draws rounded to bf16 instead
+    of quantised: w_in, w_out bf16 and no scales.
     """
     d = w.d_model
     g = _stream(device, layer, "w_in", seed)
     w_in = torch.empty(d, w.n_in, dtype=torch.float32, device=device).normal_(0.0, sigma, generator=g)
+    g = _stream(device, layer, "gamma", seed)
+    gamma = (1.0 + torch.empty(d, dtype=torch.float32, device=device).normal_(0.0, 0.02, generator=g)
+             ).to(torch.bfloat16)
+    if w.weights == "bf16":
+        w_in = w_in.to(torch.bfloat16)
+        g = _stream(device, layer, "w_out", seed)
+        w_out = torch.empty(w.k_out, d, dtype=torch.float32, device=device).normal_(0.0, sigma, generator=g)
+        return {"w_in": w_in, "w_out": w_out.to(torch.bfloat16), "gamma": gamma}
     q_in, s_in = quantize_per_channel(w_in)
     del w_in
     g = _stream(device, layer, "w_out", seed)
     w_out = torch.empty(w.k_out, d, dtype=torch.float32, device=device).normal_(0.0, sigma, generator=g)
     q_out, s_out = quantize_per_channel(w_out)
     del w_out
-    g = _stream(device, layer, "gamma", seed)
-    gamma = (1.0 + torch.empty(d, dtype=torch.float32, device=device).normal_(0.0, 0.02, generator=g)
-             ).to(torch.bfloat16)
     return {"w_in": q_in, "s_in": s_in, "w_out": q_out, "s_out": s_out, "gamma": gamma}
 
 
