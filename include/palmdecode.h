@@ -76,6 +76,11 @@ enum {
  * most 32 query heads share a K/V head; each projection
  * matrix smaller than 4 GiB; batch 1..256; L_ctx a multiple of 32.  Anything else
  * is refused with PD_ERR_SHAPE by every call that takes the description. */
+/* flags bit: w_in and w_out are bf16 with no scales, the unquantised format that
+ * Section 4.4 compares the int8 weights of Section 3.6 with.  Twice the weight
+ * bytes per step; everything else (layouts, caches, calls) is unchanged. */
+#define PD_FLAG_BF16_WEIGHTS 1
+
 typedef struct pd_model_desc {
     int32_t n_layers;
     int32_t d_model;
@@ -85,7 +90,7 @@ typedef struct pd_model_desc {
     int32_t n_kv_heads; /* 1 = multiquery (Section 3.3), n_heads = multihead */
     float rope_base;    /* 10000 */
     float ln_eps;       /* 1e-6 */
-    int32_t flags;      /* reserved, 0 */
+    int32_t flags;      /* 0, or PD_FLAG_BF16_WEIGHTS */
 } pd_model_desc;
 
 typedef struct pd_handle pd_handle;
@@ -97,7 +102,7 @@ const char* pd_last_error(void);
  * Section 2 ("Memory costs") counts exactly these two tensors per step: the
  * weights and the KV cache; the third size is this library's own scratch. */
 
-/* Bytes of one packed layer (int8 matrices, fp32 scales and gain, 256-aligned).
+/* Bytes of one packed layer (int8 or bf16 matrices, fp32 scales and gain, 256-aligned).
  * The packed stack is n_layers such blobs back to back. */
 pd_status pd_packed_layer_bytes(const pd_model_desc* desc, size_t* bytes);
 /* Bytes of EACH of the K cache and the V cache for batch B, capacity L_ctx. */
@@ -136,7 +141,9 @@ pd_status pd_profile_read(pd_handle* h, double* total_ms, int32_t* launches);
 /* Re-tiles one layer's canonical device tensors into the packed blob at
  * `packed_layer` (device, 256-aligned, pd_packed_layer_bytes() bytes).  The
  * canonical buffers may be freed once the stream has drained.  Section 3.5
- * (tensor layouts chosen to avoid padding and copies in the matrix multiplies). */
+ * (tensor layouts chosen to avoid padding and copies in the matrix multiplies).
+ * With PD_FLAG_BF16_WEIGHTS the two matrices are bf16 (same shapes, passed through
+ * the same two pointers) and s_in, s_out are ignored (may be NULL). */
 pd_status pd_pack_layer(pd_handle* h, const int8_t* w_in, const uint16_t* s_in,
                         const int8_t* w_out, const uint16_t* s_out, const uint16_t* gamma,
                         void* packed_layer, void* stream);
@@ -144,6 +151,9 @@ pd_status pd_pack_layer(pd_handle* h, const int8_t* w_in, const uint16_t* s_in,
 /* Generic pieces of the same packing for a single [K][N] int8 matrix (K % 128
  * == 0, N % 32 == 0): packed_w gets K*N bytes. */
 pd_status pd_pack_matrix(const int8_t* w, int32_t K, int32_t N, void* packed_w, void* stream);
+/* The same for a bf16 matrix (the Section 4.4 baseline format): packed_w gets 2*K*N
+ * bytes; K*N below 2^31. */
+pd_status pd_pack_matrix_bf16(const uint16_t* w, int32_t K, int32_t N, void* packed_w, void* stream);
 
 /* One layer of the cache, canonical [B][L_ctx][dh] <-> library layout, at layer
  * index `layer` of the library-side K or V cache (`is_v` selects the V layout).
@@ -269,6 +279,12 @@ pd_status pd_qgemm_plan(int32_t B, int32_t K, int32_t N, int32_t workgroups, int
 pd_status pd_qgemm(const void* packed_w, const float* scale, const uint16_t* a, int32_t B,
                    int32_t K, int32_t N, float* out, int32_t workgroups, void* workspace,
                    size_t workspace_bytes, void* stream);
+/* out[b][n] = sum_k a[b][k] * w[k][n] with bf16 weights and no scales (the
+ * Section 4.4 baseline format): packed_w from pd_pack_matrix_bf16, otherwise as
+ * pd_qgemm (same workspace size, same plan). */
+pd_status pd_wgemm_bf16(const void* packed_w, const uint16_t* a, int32_t B, int32_t K, int32_t N,
+                        float* out, int32_t workgroups, void* workspace, size_t workspace_bytes,
+                        void* stream);
 
 /* Multiquery attention of one layer over the library-layout cache (Section 3.3):
  *   q [B][H][dh] fp32 (already rotated, unscaled), o [B][H*dh] fp32,

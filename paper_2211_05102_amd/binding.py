@@ -26,8 +26,10 @@ EXPORTS = [
     "pd_check_async", "pd_qgemm_workspace_bytes", "pd_qgemm_plan", "pd_qgemm", "pd_mqa_attend",
     "pd_graph_capture", "pd_graph_replay", "pd_graph_release", "pd_profile_read",
     "pd_packed_head_bytes", "pd_head_workspace_bytes", "pd_generate_workspace_bytes", "pd_pack_head",
-    "pd_head_logits", "pd_sample", "pd_generate", "pd_prefill",
+    "pd_head_logits", "pd_sample", "pd_generate", "pd_prefill", "pd_pack_matrix_bf16", "pd_wgemm_bf16",
 ]
+
+PD_FLAG_BF16_WEIGHTS = 1
 
 
 class ModelDesc(ctypes.Structure):
@@ -80,7 +82,8 @@ def _stream(stream) -> ctypes.c_void_p:
 def make_desc(w) -> ModelDesc:
     """`w`: any object with the workload field names."""
     return ModelDesc(w.n_layers, w.d_model, w.n_heads, w.d_head, w.d_ff,
-                     getattr(w, "n_kv_heads", 1), float(w.rope_base), float(w.ln_eps), 0)
+                     getattr(w, "n_kv_heads", 1), float(w.rope_base), float(w.ln_eps),
+                     PD_FLAG_BF16_WEIGHTS if getattr(w, "weights", "int8") == "bf16" else 0)
 
 
 def packed_layer_bytes(desc: ModelDesc) -> int:
@@ -167,6 +170,22 @@ def qgemm(packed_w: torch.Tensor, scale: torch.Tensor, a: torch.Tensor, N: int, 
                           ctypes.c_size_t(workspace.numel() * workspace.element_size()), _stream(stream)))
 
 
+def pack_matrix_bf16(w: torch.Tensor, packed: torch.Tensor, stream=None) -> None:
+    K, N = w.shape
+    assert w.dtype == torch.bfloat16 and w.is_contiguous() and packed.numel() * packed.element_size() >= 2 * K * N
+    _check(lib().pd_pack_matrix_bf16(_ptr(w), ctypes.c_int32(K), ctypes.c_int32(N), _ptr(packed), _stream(stream)))
+
+
+def wgemm_bf16(packed_w: torch.Tensor, a: torch.Tensor, N: int, out: torch.Tensor,
+               workspace: torch.Tensor, workgroups: int = 0, stream=None) -> None:
+    B, K = a.shape
+    assert a.dtype == torch.bfloat16 and a.is_contiguous()
+    assert out.dtype == torch.float32 and out.shape == (B, N) and out.is_contiguous()
+    _check(lib().pd_wgemm_bf16(_ptr(packed_w), _ptr(a), ctypes.c_int32(B), ctypes.c_int32(K),
+                               ctypes.c_int32(N), _ptr(out), ctypes.c_int32(workgroups), _ptr(workspace),
+                               ctypes.c_size_t(workspace.numel() * workspace.element_size()), _stream(stream)))
+
+
 class Decoder:
     """Owns a pd_handle; methods mirror the C entry points one to one."""
 
@@ -196,8 +215,10 @@ class Decoder:
         return ms.value, n.value
 
     def pack_layer(self, wts: dict, packed_layer: torch.Tensor, stream=None) -> None:
-        _check(lib().pd_pack_layer(self._h, _ptr(wts["w_in"]), _ptr(wts["s_in"]), _ptr(wts["w_out"]),
-                                   _ptr(wts["s_out"]), _ptr(wts["gamma"]), _ptr(packed_layer),
+        want = torch.bfloat16 if self.desc.flags & PD_FLAG_BF16_WEIGHTS else torch.int8
+        assert wts["w_in"].dtype == want and wts["w_out"].dtype == want, "weight dtype does not match the handle"
+        _check(lib().pd_pack_layer(self._h, _ptr(wts["w_in"]), _ptr(wts.get("s_in")), _ptr(wts["w_out"]),
+                                   _ptr(wts.get("s_out")), _ptr(wts["gamma"]), _ptr(packed_layer),
                                    _stream(stream)))
 
     def kv_import(self, canonical: torch.Tensor, cache: torch.Tensor, layer: int, is_v: bool, stream=None) -> None:

@@ -37,6 +37,7 @@ inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_
 
 struct Shape {
     int L, d, H, G, dh, F, n_qkv, n_in, k_out;  // G = K/V heads
+    int w16;                                    // 1: the projection matrices are bf16, no scales
 };
 
 pd_status check_desc(const pd_model_desc* m, Shape* s) {
@@ -51,14 +52,17 @@ pd_status check_desc(const pd_model_desc* m, Shape* s) {
     if ((m->n_heads * m->d_head) % 128) return fail(PD_ERR_SHAPE, "n_heads*d_head must be a multiple of 128");
     long long n_in = (long long)m->n_heads * m->d_head + 2LL * m->n_kv_heads * m->d_head + 2LL * m->d_ff;
     if (n_in > (1 << 24) || k_out > (1 << 24) || m->d_model > (1 << 20)) return fail(PD_ERR_SHAPE, "model too large");
+    if (m->flags != 0 && m->flags != PD_FLAG_BF16_WEIGHTS) return fail(PD_ERR_SHAPE, "unknown flags");
     // the kernels address each matrix through a 32-bit buffer descriptor
-    if ((long long)m->d_model * n_in >= (1ll << 32) || k_out * m->d_model >= (1ll << 32))
+    const long long wbytes = m->flags & PD_FLAG_BF16_WEIGHTS ? 2 : 1;
+    if ((long long)m->d_model * n_in * wbytes >= (1ll << 32) || k_out * m->d_model * wbytes >= (1ll << 32))
         return fail(PD_ERR_SHAPE, "a projection matrix must be smaller than 4 GiB");
     if (!(m->rope_base > 1.0f) || !(m->ln_eps > 0.0f)) return fail(PD_ERR_SHAPE, "rope_base must exceed 1 and ln_eps must be positive");
     if (s) {
         s->L = m->n_layers; s->d = m->d_model; s->H = m->n_heads; s->G = m->n_kv_heads; s->dh = m->d_head; s->F = m->d_ff;
         s->n_qkv = m->n_heads * m->d_head + 2 * m->n_kv_heads * m->d_head;
         s->n_in = (int)n_in; s->k_out = (int)k_out;
+        s->w16 = m->flags & PD_FLAG_BF16_WEIGHTS ? 1 : 0;
     }
     return PD_OK;
 }
@@ -76,8 +80,8 @@ struct PackedLayout {
 PackedLayout packed_layout(const Shape& s) {
     PackedLayout p;
     size_t o = 0;
-    p.w_in = o; o += align256((size_t)s.d * s.n_in);
-    p.w_out = o; o += align256((size_t)s.k_out * s.d);
+    p.w_in = o; o += align256((size_t)s.d * s.n_in * (1 + s.w16));
+    p.w_out = o; o += align256((size_t)s.k_out * s.d * (1 + s.w16));
     p.s_in = o; o += align256((size_t)s.n_in * 4);
     p.s_out = o; o += align256((size_t)s.d * 4);
     p.gamma = o; o += align256((size_t)s.d * 4);
@@ -290,7 +294,8 @@ pd_status run_layers(pd_handle* h, const StepArgs& a, hipStream_t st) {
         if (i == 0)
             PD_TRY_HIP(pd::launch_ln_first(a.x_in, gamma, B, s.d, h->desc.ln_eps, xres, hq, hs, nd, st), "ln_first");
         prof_mark(h, PROF_QGEMM_IN, st);
-        PD_TRY_HIP(pd::launch_qgemm(L + pl.w_in, hq, hs, part_in, B, s.d, s.n_in, pl_in, nd, st), "qgemm_in");
+        if (s.w16) PD_TRY_HIP(pd::launch_wgemm_bf16(L + pl.w_in, hq, hs, part_in, B, s.d, s.n_in, pl_in, nd, st), "wgemm_in");
+        else PD_TRY_HIP(pd::launch_qgemm(L + pl.w_in, hq, hs, part_in, B, s.d, s.n_in, pl_in, nd, st), "qgemm_in");
         prof_mark(h, PROF_QGEMM_IN, st);
         prof_mark(h, PROF_EPI_IN, st);
         PD_TRY_HIP(pd::launch_epi_in(part_in, pl_in, s_in, cs, a.positions, a.seq, cache_rows, B, s.H, s.G, s.dh, s.F, a.L_ctx, q,
@@ -301,7 +306,8 @@ pd_status run_layers(pd_handle* h, const StepArgs& a, hipStream_t st) {
                                          nullptr, actq, acts, s.k_out, blk_o, nd, st), "mqa_attend");
         prof_mark(h, PROF_ATTEND, st);
         prof_mark(h, PROF_QGEMM_OUT, st);
-        PD_TRY_HIP(pd::launch_qgemm(L + pl.w_out, actq, acts, part_out, B, s.k_out, s.d, pl_out, nd, st), "qgemm_out");
+        if (s.w16) PD_TRY_HIP(pd::launch_wgemm_bf16(L + pl.w_out, actq, acts, part_out, B, s.k_out, s.d, pl_out, nd, st), "wgemm_out");
+        else PD_TRY_HIP(pd::launch_qgemm(L + pl.w_out, actq, acts, part_out, B, s.k_out, s.d, pl_out, nd, st), "qgemm_out");
         prof_mark(h, PROF_QGEMM_OUT, st);
         const bool last = i == a.n_run - 1;
         prof_mark(h, PROF_EPI_OUT, st);
@@ -500,16 +506,27 @@ pd_status pd_pack_matrix(const int8_t* w, int32_t K, int32_t N, void* packed_w, 
 pd_status pd_pack_layer(pd_handle* h, const int8_t* w_in, const uint16_t* s_in, const int8_t* w_out,
                         const uint16_t* s_out, const uint16_t* gamma, void* packed_layer, void* stream) {
     if (!h) return fail(PD_ERR_NULL, "handle is NULL");
-    if (!w_in || !s_in || !w_out || !s_out || !gamma || !packed_layer) return fail(PD_ERR_NULL, "NULL device pointer");
-    if (!aligned(packed_layer, 256)) return fail(PD_ERR_ALIGN, "packed_layer must be 256-byte aligned");
     const Shape& s = h->s;
+    if (!w_in || !w_out || !gamma || !packed_layer || (!s.w16 && (!s_in || !s_out)))
+        return fail(PD_ERR_NULL, "NULL device pointer");
+    if (!aligned(packed_layer, 256)) return fail(PD_ERR_ALIGN, "packed_layer must be 256-byte aligned");
     const PackedLayout pl = packed_layout(s);
     unsigned char* dst = static_cast<unsigned char*>(packed_layer);
     hipStream_t st = static_cast<hipStream_t>(stream);
-    PD_TRY_HIP(pd::launch_pack_matrix(w_in, dst + pl.w_in, s.d, s.n_in, 1, s.n_qkv, s.F, st), "pack w_in");
-    PD_TRY_HIP(pd::launch_pack_matrix(w_out, dst + pl.w_out, s.k_out, s.d, 0, 0, 0, st), "pack w_out");
-    PD_TRY_HIP(pd::launch_pack_vector(s_in, reinterpret_cast<float*>(dst + pl.s_in), s.n_in, 1, s.n_qkv, s.F, st), "pack s_in");
-    PD_TRY_HIP(pd::launch_pack_vector(s_out, reinterpret_cast<float*>(dst + pl.s_out), s.d, 0, 0, 0, st), "pack s_out");
+    if (s.w16) {
+        // bf16 matrices arrive through the same two pointers; every channel scale is one
+        PD_TRY_HIP(pd::launch_pack_matrix_bf16(reinterpret_cast<const uint16_t*>(w_in), dst + pl.w_in, s.d, s.n_in, 1,
+                                               s.n_qkv, s.F, st), "pack w_in (bf16)");
+        PD_TRY_HIP(pd::launch_pack_matrix_bf16(reinterpret_cast<const uint16_t*>(w_out), dst + pl.w_out, s.k_out, s.d,
+                                               0, 0, 0, st), "pack w_out (bf16)");
+        PD_TRY_HIP(pd::launch_fill_f32(reinterpret_cast<float*>(dst + pl.s_in), s.n_in, 1.0f, st), "unit s_in");
+        PD_TRY_HIP(pd::launch_fill_f32(reinterpret_cast<float*>(dst + pl.s_out), s.d, 1.0f, st), "unit s_out");
+    } else {
+        PD_TRY_HIP(pd::launch_pack_matrix(w_in, dst + pl.w_in, s.d, s.n_in, 1, s.n_qkv, s.F, st), "pack w_in");
+        PD_TRY_HIP(pd::launch_pack_matrix(w_out, dst + pl.w_out, s.k_out, s.d, 0, 0, 0, st), "pack w_out");
+        PD_TRY_HIP(pd::launch_pack_vector(s_in, reinterpret_cast<float*>(dst + pl.s_in), s.n_in, 1, s.n_qkv, s.F, st), "pack s_in");
+        PD_TRY_HIP(pd::launch_pack_vector(s_out, reinterpret_cast<float*>(dst + pl.s_out), s.d, 0, 0, 0, st), "pack s_out");
+    }
     PD_TRY_HIP(pd::launch_pack_vector(gamma, reinterpret_cast<float*>(dst + pl.gamma), s.d, 0, 0, 0, st), "pack gamma");
     PD_TRY_HIP(pd::launch_vec_absmax(reinterpret_cast<const float*>(dst + pl.gamma), s.d,
                                      reinterpret_cast<float*>(dst + pl.gamma_absmax), st), "gamma absmax");
@@ -714,6 +731,39 @@ pd_status pd_qgemm(const void* packed_w, const float* scale, const uint16_t* a, 
     PD_TRY_HIP(pd::launch_quantize_bf16(a, wsb + q.qa, qs, B, K, 3, st), "quantize");
     PD_TRY_HIP(pd::launch_qgemm(packed_w, wsb + q.qa, qs, part, B, K, N, q.pl, 3, st), "qgemm");
     PD_TRY_HIP(pd::launch_qgemm_reduce(part, scale, out, B, N, q.pl, st), "qgemm_reduce");
+    return PD_OK;
+}
+
+pd_status pd_pack_matrix_bf16(const uint16_t* w, int32_t K, int32_t N, void* packed_w, void* stream) {
+    if (!w || !packed_w) return fail(PD_ERR_NULL, "NULL device pointer");
+    if (K < 128 || K % 128 || N < 32 || N % 32) return fail(PD_ERR_SHAPE, "K must be a multiple of 128 and N a multiple of 32");
+    if ((long long)K * N * 2 >= (1ll << 32)) return fail(PD_ERR_SHAPE, "matrix must be smaller than 4 GiB");
+    if (!aligned(packed_w, 256)) return fail(PD_ERR_ALIGN, "packed_w must be 256-byte aligned");
+    PD_TRY_HIP(pd::launch_pack_matrix_bf16(w, packed_w, K, N, 0, 0, 0, static_cast<hipStream_t>(stream)), "pack_matrix_bf16");
+    return PD_OK;
+}
+
+pd_status pd_wgemm_bf16(const void* packed_w, const uint16_t* a, int32_t B, int32_t K, int32_t N, float* out,
+                        int32_t workgroups, void* workspace, size_t workspace_bytes, void* stream) {
+    if (!packed_w || !a || !out || !workspace) return fail(PD_ERR_NULL, "NULL device pointer");
+    size_t need = 0;
+    pd_status rc = pd_qgemm_workspace_bytes(B, K, N, workgroups, &need);
+    if (rc != PD_OK) return rc;
+    if ((long long)K * N * 2 >= (1ll << 32)) return fail(PD_ERR_SHAPE, "matrix must be smaller than 4 GiB");
+    if (workspace_bytes < need) return fail(PD_ERR_WORKSPACE, "workspace too small");
+    if (!aligned(packed_w, 256) || !aligned(workspace, 256) || !aligned(a, 16) || !aligned(out, 16))
+        return fail(PD_ERR_ALIGN, "misaligned device pointer");
+    QgemmWs q = qgemm_ws(B, K, N, workgroups);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    unsigned char* wsb = static_cast<unsigned char*>(workspace);
+    float* part = reinterpret_cast<float*>(wsb + q.part);
+    float* qs = reinterpret_cast<float*>(wsb + q.qs);
+    int* nseg = reinterpret_cast<int*>(wsb + q.nseg);
+    q.pl.nseg = nseg;
+    PD_TRY_HIP(pd::launch_skq_table(q.pl, nseg, st), "segment table");
+    PD_TRY_HIP(pd::launch_quantize_bf16(a, wsb + q.qa, qs, B, K, 3, st), "quantize");
+    PD_TRY_HIP(pd::launch_wgemm_bf16(packed_w, wsb + q.qa, qs, part, B, K, N, q.pl, 3, st), "wgemm_bf16");
+    PD_TRY_HIP(pd::launch_qgemm_reduce(part, nullptr, out, B, N, q.pl, st), "qgemm_reduce");
     return PD_OK;
 }
 

@@ -103,10 +103,27 @@ __device__ __forceinline__ uint4 ld_stream(const uint4* p) {
     return make_uint4(v.x, v.y, v.z, v.w);
 }
 
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also drains
+// every outstanding global load (vmcnt(0)), which would serialise a weight
+// prefetch with each step of a streaming loop; here only the LDS counter is waited on.
+__device__ __forceinline__ void lds_barrier() {
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
 __device__ __forceinline__ float wave_max(float v) {
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
     return v;
+}
+
+// Column map of the fused input projection: packed column -> canonical column.
+// q|k|v keep their place; gate and up are interleaved in 32-column groups
+// (gate group m, then up group m) so one workgroup sees both halves of a
+// SwiGLU pair.  mode 0 = identity.
+__device__ __forceinline__ int packed_col_map(int pn, int mode, int n_qkv, int F) {
+    if (mode == 0 || pn < n_qkv) return pn;
+    int r = pn - n_qkv, pair = r >> 6, within = r & 63;
+    return within < 32 ? n_qkv + pair * 32 + within : n_qkv + F + pair * 32 + (within - 32);
 }
 
 // ---- block fixed-point activations ------------------------------------------

@@ -26,6 +26,13 @@ hipError_t launch_pack_vector(const uint16_t* src, float* dst, int N, int mode, 
 hipError_t launch_qgemm_reduce(const float* part, const float* scale, float* out, int B, int N,
                                SkqPlan pl, hipStream_t stream);
 
+// ---- wgemm.hip: the same product with bf16 weights (same plan, same partial slots)
+hipError_t launch_wgemm_bf16(const void* wp, const void* qa, const float* scale_t, float* part, int B,
+                             int K, int N, SkqPlan pl, int nd, hipStream_t stream);
+hipError_t launch_pack_matrix_bf16(const uint16_t* w, void* dst, int K, int N, int mode, int n_qkv, int F,
+                                   hipStream_t stream);
+hipError_t launch_fill_f32(float* dst, int n, float v, hipStream_t stream);
+
 // ---- attention.hip
 hipError_t launch_mqa_attend(const float* q, const void* kc_layer, const void* vc_layer,
                              const int32_t* positions, const int32_t* seq, int cache_rows, int B, int H,

@@ -38,13 +38,6 @@
 
 namespace pd {
 
-// Workgroup barrier that orders LDS traffic only.  __syncthreads() also drains
-// every outstanding global load (vmcnt(0)), which would serialise the weight
-// prefetch with each unit; here only the LDS counter is waited on.
-__device__ __forceinline__ void lds_barrier() {
-    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-}
-
 constexpr int NT = 256;  // threads per GEMM workgroup: 4 waves, one per SIMD, 512 registers each
 
 // BM: 32-row batch blocks held in accumulators; NS: 32-column subtiles per wave;
@@ -567,16 +560,6 @@ __global__ __launch_bounds__(256) void quantize_bf16_kernel(const uint16_t* __re
 
 // ---- packing ----------------------------------------------------------------
 
-// Column map of the fused input projection: packed column -> canonical column.
-// q|k|v keep their place; gate and up are interleaved in 32-column groups
-// (gate group m, then up group m) so one workgroup sees both halves of a
-// SwiGLU pair.  mode 0 = identity.
-__device__ __forceinline__ int col_map(int pn, int mode, int n_qkv, int F) {
-    if (mode == 0 || pn < n_qkv) return pn;
-    int r = pn - n_qkv, pair = r >> 6, within = r & 63;
-    return within < 32 ? n_qkv + pair * 32 + within : n_qkv + F + pair * 32 + (within - 32);
-}
-
 __global__ __launch_bounds__(256) void pack_matrix_kernel(const int8_t* __restrict__ w,
                                                           uint4* __restrict__ dst, int K, int N,
                                                           int mode, int n_qkv, int F) {
@@ -587,7 +570,7 @@ __global__ __launch_bounds__(256) void pack_matrix_kernel(const int8_t* __restri
     size_t t = idx >> 6;
     int kb = (int)(t % (size_t)(K >> 5));
     int st = (int)(t / (size_t)(K >> 5));
-    int n = col_map(st * 32 + (lane & 31), mode, n_qkv, F);
+    int n = packed_col_map(st * 32 + (lane & 31), mode, n_qkv, F);
     int k0 = kb * 32 + (lane >> 5) * 16;
     uint32_t o[4] = {0, 0, 0, 0};
 #pragma unroll
@@ -602,10 +585,10 @@ __global__ __launch_bounds__(256) void pack_vector_kernel(const uint16_t* __rest
                                                           float* __restrict__ dst, int N, int mode,
                                                           int n_qkv, int F) {
     int pn = blockIdx.x * 256 + threadIdx.x;
-    if (pn < N) dst[pn] = from_bf16(src[col_map(pn, mode, n_qkv, F)]);
+    if (pn < N) dst[pn] = from_bf16(src[packed_col_map(pn, mode, n_qkv, F)]);
 }
 
-// out[b][n] = scale[n] * sum over the slots of n's tile (fixed order)
+// out[b][n] = scale[n] * sum over the slots of n's tile (fixed order); scale NULL = ones
 __global__ __launch_bounds__(256) void qgemm_reduce_kernel(const float* __restrict__ part,
                                                            const float* __restrict__ scale,
                                                            float* __restrict__ out, int B, int N,
@@ -615,7 +598,7 @@ __global__ __launch_bounds__(256) void qgemm_reduce_kernel(const float* __restri
     const int ns = pl.nseg[n / pl.tile_cols];
     float acc = 0.f;
     for (int s = 0; s < ns; s++) acc += part[((size_t)s * pl.rows + b) * N + n];
-    out[(size_t)b * N + n] = scale[n] * acc;
+    out[(size_t)b * N + n] = scale ? scale[n] * acc : acc;
 }
 
 // ---- host launchers -----------------------------------------------------------

@@ -39,7 +39,8 @@ def test_every_declared_symbol_is_exported(binding):
 def test_sizes(binding):
     from workloads import WORKLOADS
     from workloads import configs as C
-    for w in WORKLOADS.values():
+    from workloads import VARIANTS
+    for w in list(WORKLOADS.values()) + [VARIANTS["c3_62b_bf16w"]]:
         d = binding.make_desc(w)
         assert binding.kv_cache_bytes(d, w.batch, w.l_ctx) * 2 == C.kv_alloc_bytes(w)
         pl = binding.packed_layer_bytes(d)
@@ -58,6 +59,18 @@ def test_bad_descriptions_are_rejected(binding):
         assert e.value.code == binding.PD_ERR_SHAPE
     with pytest.raises(binding.PdError):
         binding.kv_cache_bytes(binding.make_desc(w), 1, 100)  # L_ctx not a multiple of 32
+    d = binding.make_desc(w)
+    d.flags = 2  # not a defined flag
+    with pytest.raises(binding.PdError) as e:
+        binding.packed_layer_bytes(d)
+    assert e.value.code == binding.PD_ERR_SHAPE
+    # a matrix of 4 GiB or more: fine as int8 (2^31 bytes), refused as bf16 (2^32 bytes)
+    big = w.with_(d_model=32768, n_heads=28, d_head=256, d_ff=28672)  # n_in = 7168 + 512 + 57344 = 65024; 32768*65024 < 2^31
+    assert binding.packed_layer_bytes(binding.make_desc(big)) > 0
+    big16 = big.with_(weights="bf16", d_ff=30208)  # n_in = 68096: 32768 * 68096 * 2 >= 2^32
+    with pytest.raises(binding.PdError) as e:
+        binding.packed_layer_bytes(binding.make_desc(big16))
+    assert e.value.code == binding.PD_ERR_SHAPE
     with pytest.raises(binding.PdError):
         binding.workspace_bytes(binding.make_desc(w), 0, 128)
 

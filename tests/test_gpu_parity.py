@@ -132,6 +132,50 @@ def test_qgemm_random_vs_oracle(pd):
     assert np.max(np.abs(got - want)) <= 2e-5 * np.max(np.abs(want))
 
 
+# ---- the same product with bf16 weights (Section 4.4 baseline format)
+
+def run_wgemm(pd, a_bf16, w_bf16, k_splits):
+    from paper_2211_05102_amd import binding
+    B, K = a_bf16.shape
+    N = w_bf16.shape[1]
+    packed = torch.empty(2 * K * N, dtype=torch.uint8, device="cuda")
+    binding.pack_matrix_bf16(w_bf16.cuda().contiguous(), packed)
+    ws = torch.empty(binding.qgemm_workspace_bytes(B, K, N, k_splits), dtype=torch.uint8, device="cuda")
+    out = torch.full((B, N), float("nan"), dtype=torch.float32, device="cuda")
+    binding.wgemm_bf16(packed, a_bf16.cuda().contiguous(), N, out, ws, k_splits)
+    torch.cuda.synchronize()
+    return out.cpu()
+
+
+@pytest.mark.parametrize("B,K,N,S", [
+    (1, 128, 32, 1), (1, 256, 2432, 0), (8, 1280, 256, 3), (33, 512, 96, 2), (64, 4096, 544, 0),
+    (64, 20480, 256, 16), (32, 10752, 160, 7), (130, 384, 320, 1), (256, 1024, 288, 4),
+])
+def test_wgemm_bf16_exact_integers(pd, B, K, N, S):
+    # integer activations in [-2, 2]; weights = integers in [-15, 15] times a power of two per
+    # column (exact in bf16): every partial sum is such an integer below 2^24 times that power,
+    # so the fp32 sums of the matrix pipe are exact in any order and any K-split
+    g = torch.Generator().manual_seed(B * 137 + K + N)
+    a = torch.randint(-2, 3, (B, K), generator=g).to(torch.bfloat16)
+    wi = torch.randint(-15, 16, (K, N), generator=g)
+    ex = torch.randint(-8, 3, (N,), generator=g)
+    w = (wi.float() * torch.pow(2.0, ex.float())[None, :]).to(torch.bfloat16)
+    want = (a.long() @ wi).double() * torch.pow(2.0, ex.double())[None, :]
+    got = run_wgemm(pd, a, w, S)
+    assert torch.equal(got.double(), want), f"max diff {float((got.double() - want).abs().max())}"
+
+
+def test_wgemm_bf16_random_vs_oracle(pd):
+    B, K, N = 24, 2048, 416
+    g = torch.Generator().manual_seed(4)
+    a = torch.randn(B, K, generator=g).to(torch.bfloat16)
+    w = (torch.randn(K, N, generator=g) * 0.02).to(torch.bfloat16)
+    want = oracle.wmatmul_bf16(widen(bits_np(a)), bits_np(w))
+    got = run_wgemm(pd, a, w, 0).double().numpy()
+    # inputs are exact on both sides; only the fp32 sums of the matrix pipe differ
+    assert np.max(np.abs(got - want)) <= 2e-5 * np.max(np.abs(want))
+
+
 # -------------------------------------------------------------- attention ---
 
 @pytest.mark.parametrize("H,dh,L,pos", [
@@ -318,6 +362,22 @@ def test_decode_step_small_shapes(pd, shape):
     assert scaled <= MAX_SCALED and rel <= REL_L2, (scaled, rel)
 
 
+@pytest.mark.parametrize("shape", [
+    (2, 384, 4, 1, 64, 384, 5, 96, [95, 0, 31, 32, 50]),
+    (3, 512, 5, 1, 128, 384, 37, 160, None),
+    (1, 1024, 32, 1, 256, 1024, 70, 64, None),
+    (2, 256, 4, 4, 64, 512, 130, 64, None),       # multihead K/V, three row groups
+])
+def test_decode_step_bf16_weights_small_shapes(pd, shape):
+    # the bf16-weight format of Section 4.4: same step, matrices unquantised
+    L_, d, H, G, dh, F, B, L, pos = shape
+    w = Workload("w16", L_, d, H, dh, F, B, L, positions="ragged", pos_lo=0, pos_hi=L, n_kv_heads=G,
+                 weights="bf16")
+    st, scaled, rel, _, _ = run_stack_parity(pd, w, name=f"bf16w{shape[:8]}", positions=pos)
+    assert scaled <= MAX_SCALED and rel <= REL_L2, (scaled, rel)
+    assert_bitwise_repeatable(st, st.step())
+
+
 def _random_shapes(n, seed):
     rng = np.random.default_rng(seed)
     shapes = []
@@ -395,6 +455,16 @@ def test_decode_step_62b_shaped_sampled_rows(pd, big_memory):
     # the append check covers all 64
     w = WORKLOADS["c3_62b"]
     st, scaled, rel, _, _ = run_stack_parity(pd, w, rows=[0, 63, 17, 42, 5, 30])
+    assert scaled <= MAX_SCALED and rel <= REL_L2, (scaled, rel)
+    assert_bitwise_repeatable(st, st.x_out)
+
+
+def test_decode_step_62b_shaped_bf16_weights_sampled_rows(pd, big_memory):
+    # the 62B-shaped layer with unquantised bf16 matrices (Section 4.4 baseline), 8 layers deep,
+    # in the launch configuration the benchmark times for that variant
+    from workloads import VARIANTS
+    w = VARIANTS["c3_62b_bf16w"].with_(n_layers=8)
+    st, scaled, rel, _, _ = run_stack_parity(pd, w, rows=[0, 63, 29], name="c3_62b_bf16w x8")
     assert scaled <= MAX_SCALED and rel <= REL_L2, (scaled, rel)
     assert_bitwise_repeatable(st, st.x_out)
 
