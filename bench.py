@@ -15,7 +15,8 @@ Prints ONE JSON line.
                        fraction of the HBM peak, int8 matrix-pipe utilisation, two-phase bound
   generate             the generation loop (64 steps, sampling head included): ms per token
   prefill              2048 input tokens of one sequence through the same stack (Section 2.2)
-  variants             multiquery vs multihead twin of the 62B-shaped stack (Section 4.2)
+  variants             multiquery vs multihead twin of the 62B-shaped stack (Section 4.2); the
+                       62B-shaped stack with bf16 instead of int8 weights (Section 4.4)
   copy_ceiling         a plain device-to-device copy, the practical bandwidth ceiling
   cpu_baseline         the fp64 oracle on a bounded sample of the headline workload
 """
@@ -111,18 +112,25 @@ def summarize(w, positions, ms):
     wbytes = C.weight_bytes(w)
     kvbytes = C.kv_read_bytes(w, positions)
     s = ms * 1e-3
-    int8_ops = 2.0 * wbytes * w.batch * ACT_PLANES
+    # matrix-pipe work of the projections as this library computes them: ACT_PLANES passes of
+    # the activations' digit planes over every weight (int8 passes, or bf16 passes for a
+    # bf16-weight stack)
+    w16 = w.weights == "bf16"
+    n_weights = wbytes // (2 if w16 else 1)
+    int8_ops = 2.0 * n_weights * w.batch * ACT_PLANES
+    pipe_peak = BF16_PEAK_FLOPS if w16 else INT8_PEAK_OPS
     return {
         "ms_per_step": ms,
         "tokens_per_s": w.batch / s,
         "GB/s": bytes_step / s / 1e9,
         "hbm_peak_frac": bytes_step / s / 1e9 / HBM_PEAK_GBPS,
-        "int8_mfma_util": int8_ops / s / INT8_PEAK_OPS,
+        ("bf16_mfma_util" if w16 else "int8_mfma_util"): int8_ops / s / pipe_peak,
         # lower bounds of the step: bytes at the HBM peak; projections on the matrix pipe (as this
         # library computes them: 3 int8 planes; and as one bf16 pass) followed by the KV stream
         "bound_ms": {"hbm": bytes_step / (HBM_PEAK_GBPS * 1e9) * 1e3,
-                     "two_phase_int8x3": (int8_ops / INT8_PEAK_OPS + kvbytes / (HBM_PEAK_GBPS * 1e9)) * 1e3,
-                     "two_phase_bf16": (2.0 * wbytes * w.batch / BF16_PEAK_FLOPS + kvbytes / (HBM_PEAK_GBPS * 1e9)) * 1e3},
+                     ("two_phase_bf16x3" if w16 else "two_phase_int8x3"):
+                         (int8_ops / pipe_peak + kvbytes / (HBM_PEAK_GBPS * 1e9)) * 1e3,
+                     "two_phase_bf16": (2.0 * n_weights * w.batch / BF16_PEAK_FLOPS + kvbytes / (HBM_PEAK_GBPS * 1e9)) * 1e3},
     }
 
 
@@ -399,7 +407,8 @@ def main():
         for name, k, e in (("c1_tiny", 50, 20), ("c2_8b", 30, 10), ("c4_540b_shard8", 10, 4), ("c5_62b_long", 6, 0)):
             if name != args.workload:
                 out["per_config"][name] = time_workload(WORKLOADS[name], steps=k, warmup=2, eager_steps=e)
-        # Section 4.2: the same stack with one K/V head per query head reads H/2 times the KV bytes
+        # Section 4.2: the same stack with one K/V head per query head reads H/2 times the KV bytes;
+        # Section 4.4: the same stack with bf16 weights reads twice the weight bytes
         out["variants"] = {name: time_workload(v, steps=5, warmup=2) for name, v in VARIANTS.items()}
     if not args.no_cpu_baseline:
         note("cpu baseline (oracle on host cores)")
