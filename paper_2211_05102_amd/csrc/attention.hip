@@ -35,36 +35,45 @@ namespace pd {
 
 // o[b][h*dh + c] = sum_s w_s O_s[c] / sum_s w_s l_s,  w_s = 2^(m_s - max m), splits in index order.
 // One workgroup per scale block of the row (blk_o chunks of 128 elements, at most
-// 16); each wave takes every fourth chunk, two adjacent channels per lane.  The
-// result goes out as fp32 (`o`) and/or in block fixed point as the first
-// H*dh/128 chunks of the output projection's operand (`actq`, `acts`).
-// MAXS: upper bound of the live splits, so that every load of the sums below is
-// issued before any is needed.
+// 16), one wavefront per chunk (blockDim = 64 * blk_o), two adjacent channels per
+// lane: every load of the row's partials is in flight at once, so the kernel is one
+// round trip to memory however many chunks the block has.  The result goes out as
+// fp32 (`o`) and/or in block fixed point as the first H*dh/128 chunks of the output
+// projection's operand (`actq`, `acts`).
+// MAXS: upper bound of the live splits (0: run-time loop, for long contexts cut into
+// many small splits).
+__device__ __forceinline__ float combine_block_max(float v, float* red, int waves) {
+    v = wave_max(v);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+    __syncthreads();
+    float t = red[0];
+    for (int w = 1; w < waves; w++) t = fmaxf(t, red[w]);
+    return t;
+}
+
 template <int MAXS>
-__global__ __launch_bounds__(256) void mqa_combine_kernel(
+__global__ __launch_bounds__(1024) void mqa_combine_kernel(
     const float* __restrict__ opart, const float* __restrict__ ml,
     const int32_t* __restrict__ positions, int H, int G, int dh, int L_ctx, int bps, int nsplit,
     float* __restrict__ o, unsigned char* __restrict__ actq, float* __restrict__ acts,
     int k_out, int blk_o, int nd) {
-    __shared__ float red[4];
+    __shared__ float red[16];
     const int b = blockIdx.y;
     const int P = positions[b];
     if (P < 0 || P >= L_ctx) return;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int c_lo = blockIdx.x * blk_o;
-    const int c_hi = c_lo + blk_o < (H * dh >> 7) ? c_lo + blk_o : (H * dh >> 7);
+    const int j = blockIdx.x * blk_o + wave;  // this wave's chunk
+    const bool in_row = j < (H * dh >> 7);
     const int live = ((P >> 5) + bps) / bps;  // ceil(nblk / bps), nblk = P/32 + 1
-    float o0[4], o1[4], mx = 0.f;
-#pragma unroll
-    for (int k = 0; k < 4; k++) {
-        const int j = c_lo + wave + 4 * k;
-        o0[k] = o1[k] = 0.f;
-        if (j < c_hi) {
-            const int idx = j * QCHUNK + 2 * lane;  // idx and idx + 1 lie in the same head
-            const int h = idx / dh, c = idx - h * dh;
-            // K/V head h / per of row b is pseudo-sequence b*G + h/per; it holds `per` query heads
-            const int per = H / G;
-            const size_t row0 = ((size_t)b * G + h / per) * nsplit * per + h % per;
+    float o0 = 0.f, o1 = 0.f;
+    if (in_row) {
+        const int idx = j * QCHUNK + 2 * lane;  // idx and idx + 1 lie in the same head
+        const int h = idx / dh, c = idx - h * dh;
+        // K/V head h / per of row b is pseudo-sequence b*G + h/per; it holds `per` query heads
+        const int per = H / G;
+        const size_t row0 = ((size_t)b * G + h / per) * nsplit * per + h % per;
+        float n0 = 0.f, n1 = 0.f, den = 0.f;
+        if constexpr (MAXS > 0) {
             f32x2 mlv[MAXS], ov[MAXS];
 #pragma unroll
             for (int s = 0; s < MAXS; s++) {
@@ -76,7 +85,6 @@ __global__ __launch_bounds__(256) void mqa_combine_kernel(
 #pragma unroll
             for (int s = 0; s < MAXS; s++)
                 if (s < live) m_all = fmaxf(m_all, mlv[s].x);
-            float n0 = 0.f, n1 = 0.f, den = 0.f;
 #pragma unroll
             for (int s = 0; s < MAXS; s++)
                 if (s < live) {
@@ -85,56 +93,9 @@ __global__ __launch_bounds__(256) void mqa_combine_kernel(
                     n0 += w * ov[s].x;
                     n1 += w * ov[s].y;
                 }
-            o0[k] = n0 / den;
-            o1[k] = n1 / den;
-            mx = fmaxf(mx, fmaxf(fabsf(o0[k]), fabsf(o1[k])));
-            if (o) {
-                const f32x2 out = {o0[k], o1[k]};
-                *reinterpret_cast<f32x2*>(o + (size_t)b * H * dh + idx) = out;
-            }
-        }
-    }
-    if (!actq) return;
-    const float s = qscale_from_max(block_max_256(mx, red), nd);
-    const float inv = 1.0f / s;
-#pragma unroll
-    for (int k = 0; k < 4; k++) {
-        const int j = c_lo + wave + 4 * k;
-        if (j < c_hi) {
-            quantize_pair_store(o0[k], o1[k], inv, nd, lane,
-                                actq + ((size_t)b * k_out + (size_t)j * QCHUNK) * nd);
-            if (lane == 0) acts[(size_t)j * QSCALE_ROWS + b] = s;
-        }
-    }
-}
-
-// the same with a run-time number of splits (long contexts with small splits)
-__global__ __launch_bounds__(256) void mqa_combine_any_kernel(
-    const float* __restrict__ opart, const float* __restrict__ ml,
-    const int32_t* __restrict__ positions, int H, int G, int dh, int L_ctx, int bps, int nsplit,
-    float* __restrict__ o, unsigned char* __restrict__ actq, float* __restrict__ acts,
-    int k_out, int blk_o, int nd) {
-    __shared__ float red[4];
-    const int b = blockIdx.y;
-    const int P = positions[b];
-    if (P < 0 || P >= L_ctx) return;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int c_lo = blockIdx.x * blk_o;
-    const int c_hi = c_lo + blk_o < (H * dh >> 7) ? c_lo + blk_o : (H * dh >> 7);
-    const int live = ((P >> 5) + bps) / bps;
-    float o0[4], o1[4], mx = 0.f;
-#pragma unroll
-    for (int k = 0; k < 4; k++) {
-        const int j = c_lo + wave + 4 * k;
-        o0[k] = o1[k] = 0.f;
-        if (j < c_hi) {
-            const int idx = j * QCHUNK + 2 * lane;
-            const int h = idx / dh, c = idx - h * dh;
-            const int per = H / G;
-            const size_t row0 = ((size_t)b * G + h / per) * nsplit * per + h % per;
+        } else {
             float m_all = -INFINITY;
             for (int s = 0; s < live; s++) m_all = fmaxf(m_all, ml[(row0 + (size_t)s * per) * 2]);
-            float n0 = 0.f, n1 = 0.f, den = 0.f;
             for (int s = 0; s < live; s++) {
                 const size_t row = row0 + (size_t)s * per;
                 const float w = __builtin_amdgcn_exp2f(ml[row * 2] - m_all);
@@ -143,26 +104,19 @@ __global__ __launch_bounds__(256) void mqa_combine_any_kernel(
                 n0 += w * ov.x;
                 n1 += w * ov.y;
             }
-            o0[k] = n0 / den;
-            o1[k] = n1 / den;
-            mx = fmaxf(mx, fmaxf(fabsf(o0[k]), fabsf(o1[k])));
-            if (o) {
-                const f32x2 out = {o0[k], o1[k]};
-                *reinterpret_cast<f32x2*>(o + (size_t)b * H * dh + idx) = out;
-            }
+        }
+        o0 = n0 / den;
+        o1 = n1 / den;
+        if (o) {
+            const f32x2 out = {o0, o1};
+            *reinterpret_cast<f32x2*>(o + (size_t)b * H * dh + idx) = out;
         }
     }
     if (!actq) return;
-    const float s = qscale_from_max(block_max_256(mx, red), nd);
-    const float inv = 1.0f / s;
-#pragma unroll
-    for (int k = 0; k < 4; k++) {
-        const int j = c_lo + wave + 4 * k;
-        if (j < c_hi) {
-            quantize_pair_store(o0[k], o1[k], inv, nd, lane,
-                                actq + ((size_t)b * k_out + (size_t)j * QCHUNK) * nd);
-            if (lane == 0) acts[(size_t)j * QSCALE_ROWS + b] = s;
-        }
+    const float s = qscale_from_max(combine_block_max(fmaxf(fabsf(o0), fabsf(o1)), red, blockDim.x >> 6), nd);
+    if (in_row) {
+        quantize_pair_store(o0, o1, 1.0f / s, nd, lane, actq + ((size_t)b * k_out + (size_t)j * QCHUNK) * nd);
+        if (lane == 0) acts[(size_t)j * QSCALE_ROWS + b] = s;
     }
 }
 
@@ -456,13 +410,13 @@ hipError_t launch_mqa_attend(const float* q, const void* kc_layer, const void* v
         return hipErrorInvalidValue;
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    dim3 cgrid((H * dh / 128 + blk_o - 1) / blk_o, B);
+    dim3 cgrid((H * dh / 128 + blk_o - 1) / blk_o, B), cblock(64 * blk_o);  // one wave per chunk
     unsigned char* aq = reinterpret_cast<unsigned char*>(actq);
-#define PD_COMB(K) K<<<cgrid, block, 0, stream>>>(opart, ml, positions, H, G, dh, L_ctx, bps, nsplit, o, aq, acts, k_out, blk_o, nd)
+#define PD_COMB(K) K<<<cgrid, cblock, 0, stream>>>(opart, ml, positions, H, G, dh, L_ctx, bps, nsplit, o, aq, acts, k_out, blk_o, nd)
     if (nsplit <= 4) PD_COMB(mqa_combine_kernel<4>);
     else if (nsplit <= 8) PD_COMB(mqa_combine_kernel<8>);
     else if (nsplit <= 16) PD_COMB(mqa_combine_kernel<16>);
-    else PD_COMB(mqa_combine_any_kernel);
+    else PD_COMB(mqa_combine_kernel<0>);
 #undef PD_COMB
     return hipGetLastError();
 }
