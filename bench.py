@@ -18,6 +18,8 @@ Prints ONE JSON line.
   variants             multiquery vs multihead twin of the 62B-shaped stack (Section 4.2); the
                        62B-shaped stack with bf16 instead of int8 weights (Section 4.4)
   copy_ceiling         a plain device-to-device copy, the practical bandwidth ceiling
+  ceilings             measured on this GPU with the library's probe kernel: streaming read alone, the
+                       int8 matrix pipe alone, and both at the projection's 384 operations per byte
   cpu_baseline         the fp64 oracle on a bounded sample of the headline workload
 """
 import argparse
@@ -258,6 +260,41 @@ def copy_ceiling():
             "what": "torch device-to-device copy of 4 GiB, best of 5"}
 
 
+def ceiling_probes():
+    """What this GPU sustains, measured with the library's probe kernel (a streaming read with
+    int8 matrix instructions issued beside it, off the stream's critical path): the plain
+    streaming-read ceiling, the matrix pipe alone, and the two together at the projection's own
+    ratio of 384 int8 operations per weight byte (three digit planes, 64 rows).  Each figure is
+    taken after about a second of the same load, when clocks have settled."""
+    import torch
+    from paper_2211_05102_amd import binding
+    nbytes = 72 * 8388608  # 576 MiB, two buffers alternate so nothing is served from a cache
+    bufs = [torch.empty(nbytes, dtype=torch.uint8, device="cuda").fill_(i + 1) for i in range(2)]
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+    stream = torch.cuda.current_stream()
+    out = {}
+    for label, m, rnd in (("stream_only", 0, False), ("stream_plus_int8x3_constant_operands", 48, False),
+                          ("stream_plus_int8x3_random_operands", 48, True),
+                          ("matrix_pipe_random_operands", 1200, True)):
+        n = 0
+        t0 = time.perf_counter()
+        while time.perf_counter() - t0 < 0.8:  # settle the clocks under this load
+            for _ in range(20):
+                binding.ceiling_probe(bufs[n & 1], m, rnd, sink, stream)
+                n += 1
+            torch.cuda.synchronize()
+        reps = 40 if m <= 48 else 4
+        ms = event_times(lambda: binding.ceiling_probe(bufs[0], m, rnd, sink, stream), reps, stream)
+        t = statistics.median(ms) * 1e-3
+        out[label] = {"us_per_launch": t * 1e6, "GB/s": nbytes / t / 1e9,
+                      "int8_POP/s": m * 65536.0 * (nbytes / 8192) / t / 1e15, "mfma_per_8KiB_per_wave": m}
+    del bufs
+    torch.cuda.empty_cache()
+    out["what"] = ("pd_ceiling_probe: 576 MiB streamed per launch by 256 workgroups, int8 32x32x32 matrix "
+                   "instructions beside the loads; after 0.8 s of the same load")
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -398,6 +435,8 @@ def main():
     if not args.headline_only:
         note("copy ceiling")
         out["copy_ceiling"] = copy_ceiling()
+        note("ceiling probes")
+        out["ceilings"] = ceiling_probes()
         out["generate"] = time_generate(w, 64, 256000, 40, 0.9, 1.0)
         out["prefill"] = time_prefill(w, 1, 2048)
         mine = summarize(w, positions, statistics.median(t_graph))

@@ -286,6 +286,20 @@ pd_status pd_wgemm_bf16(const void* packed_w, const uint16_t* a, int32_t B, int3
                         float* out, int32_t workgroups, void* workspace, size_t workspace_bytes,
                         void* stream);
 
+/* Ceiling probe (measurement aid of the benchmark; no passage of the paper defines
+ * it).  One launch streams `buffer` (device, `bytes` a positive multiple of 8 MiB,
+ * read only) once over all compute units and, independent of the data, issues
+ * `mfma_per_unit` (a multiple of 6) int8 32x32x32 matrix instructions per wavefront
+ * for every 8 KiB the wavefront loads; 48 is the ratio of the weight-only int8
+ * projection with three digit planes at 64 rows (384 operations per weight byte,
+ * Section 3.6), 0 a plain streaming read.  random_operands != 0: the matrix operands
+ * are random bit patterns that differ between consecutive instructions (largest power
+ * draw), else constants.  `sink`: 4 bytes of device memory (never written in
+ * practice).  Time the launches yourself (events on `stream`): bytes / time and
+ * mfma_per_unit * 65536 * bytes / 8192 / time are the pair the chip sustains. */
+pd_status pd_ceiling_probe(const void* buffer, size_t bytes, int32_t mfma_per_unit,
+                           int32_t random_operands, void* sink, void* stream);
+
 /* Multiquery attention of one layer over the library-layout cache (Section 3.3):
  *   q [B][H][dh] fp32 (already rotated, unscaled), o [B][H*dh] fp32,
  *   attends over slots 0..positions[b] of layer `layer`. */

@@ -26,7 +26,7 @@ EXPORTS = [
     "pd_check_async", "pd_qgemm_workspace_bytes", "pd_qgemm_plan", "pd_qgemm", "pd_mqa_attend",
     "pd_graph_capture", "pd_graph_replay", "pd_graph_release", "pd_profile_read",
     "pd_packed_head_bytes", "pd_head_workspace_bytes", "pd_generate_workspace_bytes", "pd_pack_head",
-    "pd_head_logits", "pd_sample", "pd_generate", "pd_prefill", "pd_pack_matrix_bf16", "pd_wgemm_bf16",
+    "pd_head_logits", "pd_sample", "pd_generate", "pd_prefill", "pd_pack_matrix_bf16", "pd_wgemm_bf16", "pd_ceiling_probe",
 ]
 
 PD_FLAG_BF16_WEIGHTS = 1
@@ -184,6 +184,13 @@ def wgemm_bf16(packed_w: torch.Tensor, a: torch.Tensor, N: int, out: torch.Tenso
     _check(lib().pd_wgemm_bf16(_ptr(packed_w), _ptr(a), ctypes.c_int32(B), ctypes.c_int32(K),
                                ctypes.c_int32(N), _ptr(out), ctypes.c_int32(workgroups), _ptr(workspace),
                                ctypes.c_size_t(workspace.numel() * workspace.element_size()), _stream(stream)))
+
+
+def ceiling_probe(buffer: torch.Tensor, mfma_per_unit: int, random_operands: bool, sink: torch.Tensor,
+                  stream=None) -> None:
+    _check(lib().pd_ceiling_probe(_ptr(buffer), ctypes.c_size_t(buffer.numel() * buffer.element_size()),
+                                  ctypes.c_int32(mfma_per_unit), ctypes.c_int32(1 if random_operands else 0),
+                                  _ptr(sink), _stream(stream)))
 
 
 class Decoder:

@@ -8,7 +8,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpalmdecode.so")
-SOURCES = ["qgemm.hip", "wgemm.hip", "attention.hip", "pointwise.hip", "sampler.hip", "api.hip"]
+SOURCES = ["qgemm.hip", "wgemm.hip", "attention.hip", "pointwise.hip", "sampler.hip", "probe.hip", "api.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
@@ -23,7 +23,7 @@ def _compile(src: str) -> str:
 
 def build() -> str:
     """Compiles every source and links the shared library; always recompiles."""
-    with ThreadPoolExecutor(max_workers=6) as ex:
+    with ThreadPoolExecutor(max_workers=7) as ex:
         objs = list(ex.map(_compile, SOURCES))
     subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs], check=True)
     return LIB

@@ -767,6 +767,19 @@ pd_status pd_wgemm_bf16(const void* packed_w, const uint16_t* a, int32_t B, int3
     return PD_OK;
 }
 
+pd_status pd_ceiling_probe(const void* buffer, size_t bytes, int32_t mfma_per_unit, int32_t random_operands,
+                           void* sink, void* stream) {
+    if (!buffer || !sink) return fail(PD_ERR_NULL, "NULL device pointer");
+    if (!aligned(buffer, 16) || !aligned(sink, 4)) return fail(PD_ERR_ALIGN, "misaligned device pointer");
+    if (bytes == 0 || bytes % 8388608u) return fail(PD_ERR_SHAPE, "bytes must be a positive multiple of 8 MiB");
+    if (mfma_per_unit < 0 || mfma_per_unit % 6 || mfma_per_unit > 6000)
+        return fail(PD_ERR_RANGE, "mfma_per_unit must be a multiple of 6 in 0..6000");
+    PD_TRY_HIP(pd::launch_ceiling_probe(buffer, bytes, mfma_per_unit, random_operands ? 1 : 0,
+                                        static_cast<unsigned*>(sink), static_cast<hipStream_t>(stream)),
+               "ceiling probe");
+    return PD_OK;
+}
+
 pd_status pd_mqa_attend(pd_handle* h, int32_t layer, const float* q, const void* k_cache,
                         const void* v_cache, const int32_t* positions, int32_t B, int32_t L_ctx,
                         float* o, void* workspace, size_t workspace_bytes, void* stream) {

@@ -76,4 +76,8 @@ hipError_t launch_embed_advance(const uint16_t* embed, int d, int V, const int32
                                 uint16_t* x_next, int32_t* positions, int32_t* step, hipStream_t stream);
 hipError_t launch_step_set(int32_t* step, int value, hipStream_t stream);
 
+// ---- probe.hip
+hipError_t launch_ceiling_probe(const void* src, size_t bytes, int mfma_per_unit, int random_operands,
+                                unsigned* sink, hipStream_t stream);
+
 }  // namespace pd

@@ -1,0 +1,81 @@
+// Ceiling probe: what this GPU sustains for the projections' mix of work, measured
+// rather than looked up.  One workgroup of four wavefronts per compute unit streams a
+// buffer once with 16-byte non-temporal loads (8 in flight per lane, the pattern of a
+// bandwidth test) and, independent of the loaded data, issues `mfma_per_unit`
+// v_mfma_i32_32x32x32_i8 per wavefront for every 8 KiB the wavefront loads.  The
+// weight-only int8 projection with three digit planes at 64 rows (Section 3.6 weights;
+// 2 * 64 * 3 = 384 int8 operations per weight byte) is mfma_per_unit = 48; 0 gives the
+// plain streaming-read ceiling.  With `random_operands` the matrix operands are random
+// bit patterns that change with every instruction (the worst case for the matrix
+// pipe's power draw); without, they are constant.  The matrix work is not on the
+// stream's critical path, so what the pair (bytes/s, operations/s) falls short of the
+// two separate peaks is what the chip's power management takes, not a scheduling loss.
+#include "common.h"
+#include "kernels.h"
+
+namespace pd {
+
+__global__ __launch_bounds__(256) void ceiling_probe_kernel(const u32x4* __restrict__ src, size_t n16,
+                                                            int mfma_groups, int random_operands,
+                                                            unsigned* __restrict__ sink) {
+    constexpr int U = 8;  // 16-byte loads in flight per lane = 8 KiB per wavefront
+    const size_t per = n16 / gridDim.x;
+    const u32x4* p = src + (size_t)blockIdx.x * per + threadIdx.x;
+    const size_t iters = per / (256 * U);
+    u32x4 accx = {0, 0, 0, 0};
+    i32x16 acc[6];
+#pragma unroll
+    for (int i = 0; i < 6; i++)
+#pragma unroll
+        for (int r = 0; r < 16; r++) acc[i][r] = 0;
+    // three A and two B fragments per lane; every instruction of a group of six takes
+    // another (A, B) pair
+    i32x4 a[3], b[2];
+    unsigned s = random_operands ? threadIdx.x * 2654435761u + blockIdx.x * 40503u + 12345u : 0u;
+#pragma unroll
+    for (int i = 0; i < 5; i++) {
+        i32x4 v;
+#pragma unroll
+        for (int c = 0; c < 4; c++) {
+            s = s * 1664525u + 1013904223u;
+            v[c] = random_operands ? (int)(s ^ (s >> 13)) : 0x01010101;
+        }
+        if (i < 3) a[i] = v; else b[i - 3] = v;
+    }
+    u32x4 v[U];
+#pragma unroll
+    for (int u = 0; u < U; u++) v[u] = __builtin_nontemporal_load(p + u * 256);
+    for (size_t it = 0; it < iters; it++) {
+        u32x4 nv[U];
+        const u32x4* pn = (it + 1 < iters) ? p + 256 * U : p;  // (the last step reads its own data again)
+#pragma unroll
+        for (int u = 0; u < U; u++) nv[u] = __builtin_nontemporal_load(pn + u * 256);
+        for (int g = 0; g < mfma_groups; g++) {
+#pragma unroll
+            for (int m = 0; m < 6; m++)
+                acc[m] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[m % 3], b[m / 3], acc[m], 0, 0, 0);
+        }
+#pragma unroll
+        for (int u = 0; u < U; u++) { accx ^= v[u]; v[u] = nv[u]; }
+        p = pn;
+    }
+    int t = 0;
+#pragma unroll
+    for (int i = 0; i < 6; i++)
+#pragma unroll
+        for (int r = 0; r < 16; r++) t ^= acc[i][r];
+    if (((accx.x ^ accx.y ^ accx.z ^ accx.w) ^ (unsigned)t) == 0x9e3779b9u) sink[0] = 1;  // keeps both live
+}
+
+hipError_t launch_ceiling_probe(const void* src, size_t bytes, int mfma_per_unit, int random_operands,
+                                unsigned* sink, hipStream_t stream) {
+    // 256 workgroups (one per compute unit) x 256 lanes x 8 loads x 16 bytes per step
+    if (bytes == 0 || bytes % (256u * 256u * 8u * 16u) || mfma_per_unit < 0 || mfma_per_unit % 6 ||
+        mfma_per_unit > 6000)
+        return hipErrorInvalidValue;
+    ceiling_probe_kernel<<<dim3(256), dim3(256), 0, stream>>>(reinterpret_cast<const u32x4*>(src), bytes / 16,
+                                                              mfma_per_unit / 6, random_operands, sink);
+    return hipGetLastError();
+}
+
+}  // namespace pd
