@@ -145,11 +145,13 @@ def oracle_generate(w, st, top_k, top_p, T, n_steps, layers_cpu, kcs, vcs):
     return tokens, robust, x_bits, pos
 
 
-@pytest.mark.parametrize("top_k,top_p,T", [(1, 1.0, 1.0), (16, 0.9, 0.7)])
-def test_generate_loop_vs_oracle(pd, top_k, top_p, T):
+@pytest.mark.parametrize("top_k,top_p,T,weights", [(1, 1.0, 1.0, "int8"), (16, 0.9, 0.7, "int8"),
+                                                   (8, 0.95, 1.0, "bf16")])
+def test_generate_loop_vs_oracle(pd, top_k, top_p, T, weights):
     from paper_2211_05102_amd import harness
     n_steps, V = 8, 1024
-    w = Workload("gen", 2, 256, 4, 64, 512, 5, 96, positions="ragged", pos_lo=0, pos_hi=96 - n_steps)
+    w = Workload("gen", 2, 256, 4, 64, 512, 5, 96, positions="ragged", pos_lo=0, pos_hi=96 - n_steps,
+                 weights=weights)
     layers_cpu, kcs, vcs = [], [], []
     st = harness.GenerateStack(w, V, n_steps, on_layer=lambda l, wts, k, v: (
         layers_cpu.append({n: t.cpu() for n, t in wts.items()}), kcs.append(bits_np(k)), vcs.append(bits_np(v))))

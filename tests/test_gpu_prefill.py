@@ -35,11 +35,12 @@ def widen(b):
     (2, 256, 4, 1, 64, 512, 3, 128, [0, 0, 0], [40, 7, 1]),          # whole prefill, ragged lengths
     (2, 384, 6, 1, 128, 384, 2, 352, [17, 64], [300, 150]),          # incremental, several 256-row chunks
     (1, 512, 4, 4, 128, 256, 2, 96, [5, 0], [33, 64]),               # multihead K/V
+    (2, 256, 4, 1, 64, 384, 2, 320, [3, 0], [290, 40], "bf16"),      # bf16 weights, two chunks
 ])
 def test_prefill_vs_oracle(pd, case):
     from paper_2211_05102_amd import binding
-    L_, d, H, G, dh, F, S, L, cached, new = case
-    w = Workload("prefill", L_, d, H, dh, F, S, L, n_kv_heads=G)
+    L_, d, H, G, dh, F, S, L, cached, new = case[:10]
+    w = Workload("prefill", L_, d, H, dh, F, S, L, n_kv_heads=G, weights=case[10] if len(case) > 10 else "int8")
     dec = pd.Decoder(w)
     desc_o = oracle.make_desc(w)
     # token rows, interleaved round-robin over the sequences, each sequence in position order
