@@ -325,7 +325,7 @@ def main():
     from workloads import configs as C
     from paper_2211_05102_amd import harness
 
-    w = WORKLOADS[args.workload]
+    w = {**WORKLOADS, **VARIANTS}[args.workload]  # (the variants: profiling runs, not the headline)
     if args.layers:
         w = w.with_(n_layers=args.layers, name=f"{w.name}[{args.layers} layers]")
     t_setup = time.perf_counter()
@@ -391,7 +391,8 @@ def main():
     ms_per_step = elapsed * 1e3 / args.steps
     gbps = bytes_step / (elapsed / args.steps) / 1e9
     k_avg_s = k_ms * 1e-3 / max(k_launches, 1)
-    k_bytes = w.d_model * w.n_in  # int8 weight bytes the input projection streams per launch
+    # weight bytes the input projection streams per launch (one per int8 weight, two per bf16 weight)
+    k_bytes = w.d_model * w.n_in * (2 if w.weights == "bf16" else 1)
     k_gbps = k_bytes / k_avg_s / 1e9
     per_kernel["qgemm_in"] = {"avg_us": k_avg_s * 1e6, "launches": k_launches}
     headline = summarize(w, positions, ms_per_step)
@@ -413,18 +414,23 @@ def main():
         "vs_baseline": None,
         # int8 weights x three int8 digit planes of block fixed-point activations (23 bits + sign per
         # 128-element block) on the int8 MFMA with exact int32 sums; fp32 folds, softmax, LayerNorm
-        "dtype": "int8 weights x 3-plane int8 block-fixed-point activations, int32 sums, fp32 elsewhere",
+        "dtype": ("bf16 weights x 3-plane bf16 split of block-fixed-point activations, fp32 sums"
+                  if w.weights == "bf16" else
+                  "int8 weights x 3-plane int8 block-fixed-point activations, int32 sums, fp32 elsewhere"),
         "data": "synthetic",
         "config": {"workload": w.name, "n_layers": w.n_layers, "d_model": w.d_model,
                    "n_heads": w.n_heads, "d_head": w.d_head, "d_ff": w.d_ff, "batch": w.batch,
-                   "kv_len": w.l_ctx, "positions": w.positions, "weights": "int8 per-channel",
+                   "kv_len": w.l_ctx, "positions": w.positions,
+                   "weights": "bf16" if w.weights == "bf16" else "int8 per-channel",
                    "launch": "eager" if args.no_graph else "hipGraph replay", "setup_s": round(t_setup, 1)},
         "timing": {"graph_ms_median": statistics.median(t_graph), "graph_ms_min": min(t_graph),
                    "eager_ms_median": statistics.median(t_eager), "eager_ms_min": min(t_eager),
                    "clock": "HIP events on the launch stream, one pair per step"},
-        "int8_mfma_util": headline["int8_mfma_util"],
+        ("bf16_mfma_util" if w.weights == "bf16" else "int8_mfma_util"):
+            headline["bf16_mfma_util" if w.weights == "bf16" else "int8_mfma_util"],
         "bound_ms": headline["bound_ms"],
-        "roofline": {"bound": "hbm", "kernel": "qgemm_kernel (fused input projection)",
+        "roofline": {"bound": "hbm",
+                     "kernel": ("wgemm_bf16_kernel" if w.weights == "bf16" else "qgemm_kernel") + " (fused input projection)",
                      "achieved": k_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": k_gbps / HBM_PEAK_GBPS, "traffic": traffic_from_profile(args.workload),
                      "bytes_per_launch": k_bytes, "avg_launch_us": k_avg_s * 1e6},
@@ -437,6 +443,12 @@ def main():
         out["copy_ceiling"] = copy_ceiling()
         note("ceiling probes")
         out["ceilings"] = ceiling_probes()
+        # the dominant kernel against what the probe sustains at the same operations per byte
+        # (only meaningful for the 64-row workloads: 48 matrix instructions per 8 KiB and wave)
+        if 32 < w.batch <= 64 and w.weights == "int8":
+            probe = out["ceilings"]["stream_plus_int8x3_random_operands"]["GB/s"]
+            out["roofline"]["probe_ceiling_GBps"] = probe
+            out["roofline"]["frac_of_probe_ceiling"] = out["roofline"]["achieved"] / probe
         out["generate"] = time_generate(w, 64, 256000, 40, 0.9, 1.0)
         out["prefill"] = time_prefill(w, 1, 2048)
         mine = summarize(w, positions, statistics.median(t_graph))
