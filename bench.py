@@ -273,9 +273,10 @@ def ceiling_probes():
     sink = torch.zeros(1, dtype=torch.int32, device="cuda")
     stream = torch.cuda.current_stream()
     out = {}
-    for label, m, rnd in (("stream_only", 0, False), ("stream_plus_int8x3_constant_operands", 48, False),
-                          ("stream_plus_int8x3_random_operands", 48, True),
-                          ("matrix_pipe_random_operands", 1200, True)):
+    for label, m, rnd in (("stream_only", 0, 0), ("stream_plus_int8x3_constant_operands", 48, 0),
+                          ("stream_plus_int8x3_projection_like_operands", 48, 2),
+                          ("stream_plus_int8x3_random_operands", 48, 1),
+                          ("matrix_pipe_random_operands", 1200, 1)):
         n = 0
         t0 = time.perf_counter()
         while time.perf_counter() - t0 < 0.8:  # settle the clocks under this load

@@ -292,9 +292,10 @@ pd_status pd_wgemm_bf16(const void* packed_w, const uint16_t* a, int32_t B, int3
  * `mfma_per_unit` (a multiple of 6) int8 32x32x32 matrix instructions per wavefront
  * for every 8 KiB the wavefront loads; 48 is the ratio of the weight-only int8
  * projection with three digit planes at 64 rows (384 operations per weight byte,
- * Section 3.6), 0 a plain streaming read.  random_operands != 0: the matrix operands
- * are random bit patterns that differ between consecutive instructions (largest power
- * draw), else constants.  `sink`: 4 bytes of device memory (never written in
+ * Section 3.6), 0 a plain streaming read.  random_operands = 1: the matrix operands
+ * are uniformly random bit patterns that differ between consecutive instructions
+ * (largest power draw); 2: operands with the value statistics of the projections
+ * (bell-shaped weights and top digits, uniform lower digits); 0: constants.  `sink`: 4 bytes of device memory (never written in
  * practice).  Time the launches yourself (events on `stream`): bytes / time and
  * mfma_per_unit * 65536 * bytes / 8192 / time are the pair the chip sustains. */
 pd_status pd_ceiling_probe(const void* buffer, size_t bytes, int32_t mfma_per_unit,

@@ -186,10 +186,10 @@ def wgemm_bf16(packed_w: torch.Tensor, a: torch.Tensor, N: int, out: torch.Tenso
                                ctypes.c_size_t(workspace.numel() * workspace.element_size()), _stream(stream)))
 
 
-def ceiling_probe(buffer: torch.Tensor, mfma_per_unit: int, random_operands: bool, sink: torch.Tensor,
+def ceiling_probe(buffer: torch.Tensor, mfma_per_unit: int, random_operands: int, sink: torch.Tensor,
                   stream=None) -> None:
     _check(lib().pd_ceiling_probe(_ptr(buffer), ctypes.c_size_t(buffer.numel() * buffer.element_size()),
-                                  ctypes.c_int32(mfma_per_unit), ctypes.c_int32(1 if random_operands else 0),
+                                  ctypes.c_int32(mfma_per_unit), ctypes.c_int32(int(random_operands)),
                                   _ptr(sink), _stream(stream)))
 
 

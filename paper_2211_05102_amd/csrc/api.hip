@@ -774,7 +774,8 @@ pd_status pd_ceiling_probe(const void* buffer, size_t bytes, int32_t mfma_per_un
     if (bytes == 0 || bytes % 8388608u) return fail(PD_ERR_SHAPE, "bytes must be a positive multiple of 8 MiB");
     if (mfma_per_unit < 0 || mfma_per_unit % 6 || mfma_per_unit > 6000)
         return fail(PD_ERR_RANGE, "mfma_per_unit must be a multiple of 6 in 0..6000");
-    PD_TRY_HIP(pd::launch_ceiling_probe(buffer, bytes, mfma_per_unit, random_operands ? 1 : 0,
+    if (random_operands < 0 || random_operands > 2) return fail(PD_ERR_RANGE, "random_operands must be 0, 1 or 2");
+    PD_TRY_HIP(pd::launch_ceiling_probe(buffer, bytes, mfma_per_unit, random_operands,
                                         static_cast<unsigned*>(sink), static_cast<hipStream_t>(stream)),
                "ceiling probe");
     return PD_OK;

@@ -5,9 +5,11 @@
 // v_mfma_i32_32x32x32_i8 per wavefront for every 8 KiB the wavefront loads.  The
 // weight-only int8 projection with three digit planes at 64 rows (Section 3.6 weights;
 // 2 * 64 * 3 = 384 int8 operations per weight byte) is mfma_per_unit = 48; 0 gives the
-// plain streaming-read ceiling.  With `random_operands` the matrix operands are random
-// bit patterns that change with every instruction (the worst case for the matrix
-// pipe's power draw); without, they are constant.  The matrix work is not on the
+// plain streaming-read ceiling.  random_operands = 1: the matrix operands are uniformly
+// random bit patterns that change with every instruction (the worst case for the matrix
+// pipe's power draw); 2: operands with the value statistics of the projections (weights
+// bell-shaped around zero with sigma about 33 of 127, the top digit plane likewise, the
+// two lower digit planes uniform); 0: constants.  The matrix work is not on the
 // stream's critical path, so what the pair (bytes/s, operations/s) falls short of the
 // two separate peaks is what the chip's power management takes, not a scheduling loss.
 #include "common.h"
@@ -30,15 +32,26 @@ __global__ __launch_bounds__(256) void ceiling_probe_kernel(const u32x4* __restr
         for (int r = 0; r < 16; r++) acc[i][r] = 0;
     // three A and two B fragments per lane; every instruction of a group of six takes
     // another (A, B) pair
+    // (a[0]: top digit plane, a[1], a[2]: lower planes, b[]: weights)
     i32x4 a[3], b[2];
     unsigned s = random_operands ? threadIdx.x * 2654435761u + blockIdx.x * 40503u + 12345u : 0u;
+    auto next = [&]() { s = s * 1664525u + 1013904223u; return s ^ (s >> 13); };
 #pragma unroll
     for (int i = 0; i < 5; i++) {
         i32x4 v;
 #pragma unroll
         for (int c = 0; c < 4; c++) {
-            s = s * 1664525u + 1013904223u;
-            v[c] = random_operands ? (int)(s ^ (s >> 13)) : 0x01010101;
+            if (random_operands == 2 && (i == 0 || i >= 3)) {
+                unsigned word = 0;
+                for (int byte = 0; byte < 4; byte++) {  // sum of four uniform values in [-28, 28]: sigma 33
+                    int t = 0;
+                    for (int k = 0; k < 4; k++) t += (int)(next() % 57u) - 28;
+                    word |= (unsigned)(t & 0xff) << (8 * byte);
+                }
+                v[c] = (int)word;
+            } else {
+                v[c] = random_operands ? (int)next() : 0x01010101;
+            }
         }
         if (i < 3) a[i] = v; else b[i - 3] = v;
     }
@@ -74,7 +87,7 @@ hipError_t launch_ceiling_probe(const void* src, size_t bytes, int mfma_per_unit
         mfma_per_unit > 6000)
         return hipErrorInvalidValue;
     ceiling_probe_kernel<<<dim3(256), dim3(256), 0, stream>>>(reinterpret_cast<const u32x4*>(src), bytes / 16,
-                                                              mfma_per_unit / 6, random_operands, sink);
+                                                              mfma_per_unit / 6, random_operands, sink);  // 0, 1 or 2
     return hipGetLastError();
 }
 
