@@ -108,6 +108,25 @@ def test_argument_errors_come_before_any_launch(binding):
     dec.set_option("gemm_workgroups_in", 0)
     assert L.pd_status_string(i32(-7)).decode().startswith("position")
     dec.close()
+    # the bf16-weight entries and the ceiling probe
+    sz = ctypes.c_size_t
+    assert L.pd_pack_matrix_bf16(null, i32(128), i32(32), fake, null) == binding.PD_ERR_NULL
+    assert L.pd_pack_matrix_bf16(fake, i32(100), i32(32), fake, null) == binding.PD_ERR_SHAPE
+    assert L.pd_pack_matrix_bf16(fake, i32(65536), i32(32768), fake, null) == binding.PD_ERR_SHAPE  # 4 GiB as bf16
+    assert L.pd_pack_matrix_bf16(fake, i32(128), i32(32), odd, null) == binding.PD_ERR_ALIGN
+    assert L.pd_wgemm_bf16(fake, null, i32(1), i32(128), i32(32), fake, i32(0), fake, big, null) == binding.PD_ERR_NULL
+    assert L.pd_wgemm_bf16(fake, fake, i32(300), i32(128), i32(32), fake, i32(0), fake, big, null) == binding.PD_ERR_SHAPE
+    assert L.pd_wgemm_bf16(fake, fake, i32(1), i32(128), i32(32), fake, i32(0), fake, sz(16), null) == binding.PD_ERR_WORKSPACE
+    assert L.pd_ceiling_probe(null, sz(8388608), i32(48), i32(1), fake, null) == binding.PD_ERR_NULL
+    assert L.pd_ceiling_probe(fake, sz(1000), i32(48), i32(1), fake, null) == binding.PD_ERR_SHAPE
+    assert L.pd_ceiling_probe(fake, sz(8388608), i32(47), i32(1), fake, null) == binding.PD_ERR_RANGE
+    assert L.pd_ceiling_probe(fake, sz(8388608), i32(48), i32(3), fake, null) == binding.PD_ERR_RANGE
+    # a handle for bf16 weights takes no scale vectors; one for int8 weights needs them
+    dec16 = binding.Decoder(w.with_(weights="bf16"))
+    assert L.pd_pack_layer(dec16._h, fake, null, fake, null, fake, odd, null) == binding.PD_ERR_ALIGN  # past the NULL check
+    dec8 = binding.Decoder(w)
+    assert L.pd_pack_layer(dec8._h, fake, null, fake, null, fake, fake, null) == binding.PD_ERR_NULL
+    dec16.close(); dec8.close()
 
 
 # ---- host logic: the deterministic work split of the projections ----------------
