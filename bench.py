@@ -447,7 +447,7 @@ def main():
         # the dominant kernel against what the probe sustains at the same operations per byte
         # (only meaningful for the 64-row workloads: 48 matrix instructions per 8 KiB and wave)
         if 32 < w.batch <= 64 and w.weights == "int8":
-            probe = out["ceilings"]["stream_plus_int8x3_random_operands"]["GB/s"]
+            probe = out["ceilings"]["stream_plus_int8x3_projection_like_operands"]["GB/s"]
             out["roofline"]["probe_ceiling_GBps"] = probe
             out["roofline"]["frac_of_probe_ceiling"] = out["roofline"]["achieved"] / probe
         out["generate"] = time_generate(w, 64, 256000, 40, 0.9, 1.0)

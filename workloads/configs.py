@@ -69,7 +69,7 @@ WORKLOADS: Dict[str, Workload] = {
                             positions="ragged", pos_lo=4096, pos_hi=8192),
 }
 
-# Variants for the comparisons of Section 4.2 / Section 4.4 (not BASELINE workloads): the
+# Variants for the comparisons of Section 4.2 / Section 4.4 (not among the five named workloads): the
 # multihead twin of the 62B-shaped stack (one K/V head per query head, d_head 128 as in the
 # paper's multihead variant) and the multiquery stack at the batch that twin fits at.
 VARIANTS: Dict[str, Workload] = {
