@@ -176,6 +176,21 @@ def test_wgemm_bf16_random_vs_oracle(pd):
     assert np.max(np.abs(got - want)) <= 2e-5 * np.max(np.abs(want))
 
 
+def test_ceiling_probe_reads_only(pd):
+    # the benchmark's probe kernel streams a buffer and issues matrix instructions beside the
+    # loads: it must leave the buffer and its sink untouched in every operand mode
+    from paper_2211_05102_amd import binding
+    buf = torch.randint(0, 255, (2 * 8388608,), dtype=torch.uint8, device="cuda")
+    ref = buf.clone()
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+    for m, mode in ((0, 0), (48, 0), (48, 1), (48, 2), (6, 1)):
+        binding.ceiling_probe(buf, m, mode, sink)
+    torch.cuda.synchronize()
+    assert torch.equal(buf, ref) and int(sink.item()) == 0
+    with pytest.raises(binding.PdError):
+        binding.ceiling_probe(buf[:1000], 48, 1, sink)
+
+
 # -------------------------------------------------------------- attention ---
 
 @pytest.mark.parametrize("H,dh,L,pos", [
