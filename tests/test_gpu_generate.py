@@ -212,3 +212,66 @@ def test_generate_rejects_bad_sampling_arguments(pd):
         with pytest.raises(pd.PdError) as e:
             st.generate(k, p, T, False)
         assert e.value.code == binding.PD_ERR_RANGE
+
+
+def test_generate_62b_shaped_first_tokens_sampled_rows(pd):
+    # the generation loop in the configuration the benchmark times (62B-shaped stack, batch 64,
+    # 256,000-entry vocabulary, top-k 40 / top-p 0.9, graph replay), two steps that fill the cache;
+    # the oracle follows three sequences through the first step (stack, head, draw)
+    import gc
+    from workloads import WORKLOADS
+    from paper_2211_05102_amd import harness
+    gc.collect()
+    torch.cuda.empty_cache()
+    n_steps, V, top_k, top_p, T = 2, 256000, 40, 0.9, 1.0
+    base = WORKLOADS["c3_62b"]
+    start = base.l_ctx - n_steps
+    w = base.with_(positions="ragged", pos_lo=start, pos_hi=start + 1)
+    rows = [0, 63, 17]
+    desc = oracle.make_desc(w)
+    x_in = synth.hidden_state(w, "cuda")
+    x64 = oracle.bf16_bits_to_f64_fast(bits_np(x_in)[rows])
+    pos = np.full(len(rows), start, dtype=np.int32)
+
+    def follow(l, wts, k, v):
+        oracle.decode_layer(desc, {n: t.cpu() for n, t in wts.items()}, bits_np(k[rows]), bits_np(v[rows]), pos, x64,
+                            w.l_ctx)
+        if l % 16 == 15:
+            print(f"[generate 62b] oracle through layer {l + 1}/{w.n_layers}", flush=True)
+
+    st = harness.GenerateStack(w, V, n_steps, on_layer=follow, x_in=x_in)
+    hidden = oracle.bf16_bits_to_f64_fast(oracle.f64_to_bf16_bits(x64))  # the stack hands bf16 to the head
+    logits = oracle.head_logits(hidden, st.head["gamma_f"], st.head["w_vocab"], st.head["s_vocab"], w.ln_eps)
+    u = st.uniforms.cpu().numpy()
+    stream = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(stream):
+        st.generate(top_k, top_p, T, True, stream)
+    stream.synchronize()
+    st.dec.check_async(st.gen_workspace, stream)
+    tok = st.tokens.cpu().numpy()
+    assert tok.shape == (n_steps, w.batch) and tok.min() >= 0 and tok.max() < V
+    compared = 0
+    for i, b in enumerate(rows):
+        want, _, _ = oracle.sample_topk_topp(logits[i], top_k, top_p, T, float(u[0, b]))
+        gap, safe = decision_margins(logits[i], top_k, top_p, T, float(u[0, b]), eps=1e-3)
+        print(f"[generate 62b] row {b}: gpu {tok[0, b]} oracle {want} gap {gap:.2e} safe {safe}", flush=True)
+        if gap > 1e-3 and safe:
+            assert tok[0, b] == want, (b, tok[0, b], want)
+            compared += 1
+    assert compared >= 1
+    # state handed back: every position advanced by two, the input is the embedding of the last token
+    assert torch.equal(st.positions.cpu(), torch.full((w.batch,), start + n_steps, dtype=torch.int32))
+    assert np.array_equal(bits_np(st.x_in), bits_np(st.embed[torch.from_numpy(tok[-1]).long().cuda()]))
+    # exactly the last two slots of every row were appended (first, middle and last layer)
+    t = torch.arange(w.l_ctx, device="cuda")[None, :]
+    want_changed = (t >= start).expand(w.batch, -1)
+    for l in (0, 31, 63):
+        ka, va = st.export_kv(l)
+        k0, v0 = synth.kv_layer(w, l, "cuda")
+        for got, ref in ((ka, k0), (va, v0)):
+            changed = (got.view(torch.int16) != ref.view(torch.int16)).any(dim=2)
+            assert torch.equal(changed, want_changed), l
+    del st
+    gc.collect()
+    torch.cuda.empty_cache()
