@@ -125,3 +125,83 @@ def test_prefill_flags_bad_sequence_ids(pd):
         dec.check_async(ws)
     assert e.value.code == binding.PD_ERR_POSITION
     assert not torch.equal(kc.view(torch.int16), k0.view(torch.int16))  # rows 0 and 1 did append
+
+
+def test_prefill_62b_shaped_first_tokens_and_decode_consistency(pd):
+    # prefill at the size the benchmark times: 256-row chunks through the 62B-shaped stack, attention
+    # lengths up to 2048.  Here the sequence continues a cached prefix of 1024 seeded tokens with 1024
+    # new ones (incremental prefill, Section 3.5): the oracle follows the first four new tokens.  (The
+    # very first tokens of a sequence prefilled from nothing attend to one to four slots; over 64
+    # layers of these synthetic weights the fp64 definition itself, re-run with 2^-24 noise, moves
+    # their outputs by 0.2 scaled-max, so they cannot carry an elementwise comparison.)  The last
+    # token is checked against the decode step of the same token on a cache prefilled up to it
+    # (Section 2.2: both phases compute the same function), and the slots it appends against each other.
+    import gc
+    from workloads import WORKLOADS
+    from paper_2211_05102_amd import binding, harness
+    gc.collect()
+    torch.cuda.empty_cache()
+    base = WORKLOADS["c3_62b"]
+    P0 = base.l_ctx // 2
+    N = base.l_ctx - P0
+    w = base.with_(batch=1, name="c3_62b[prefill]")
+    desc_o = oracle.make_desc(w)
+    g = torch.Generator(device="cuda").manual_seed(11)
+    x = torch.randn(N, w.d_model, generator=g, device="cuda").to(torch.bfloat16)
+    first = 4
+    x64 = oracle.bf16_bits_to_f64_fast(bits_np(x[:first]))
+    pos4 = np.arange(P0, P0 + first, dtype=np.int32)
+
+    def follow(l, wts, k, v):  # k, v: the seeded prefix, NaN / Inf from slot P0 on
+        oracle.decode_layer(desc_o, {n: t.cpu() for n, t in wts.items()}, bits_np(k), bits_np(v), pos4, x64, w.l_ctx,
+                            cache_row=np.zeros(first, dtype=np.int32))
+        if l % 16 == 15:
+            print(f"[prefill 62b] oracle through layer {l + 1}/{w.n_layers}", flush=True)
+
+    st = harness.DeviceStack(w, poison_unused=True, on_layer=follow,
+                             positions=torch.full((1,), P0 - 1, dtype=torch.int32), x_in=x[:1].clone())
+    ws = torch.empty(binding.workspace_bytes(st.desc, 256, w.l_ctx), dtype=torch.uint8, device="cuda")
+    seq = torch.zeros(N, dtype=torch.int32, device="cuda")
+    pos = torch.arange(P0, P0 + N, dtype=torch.int32, device="cuda")
+    out = torch.full((N, w.d_model), float("nan"), dtype=torch.bfloat16, device="cuda")
+    k_start, v_start = st.k_cache.clone(), st.v_cache.clone()
+    st.dec.prefill(st.packed, st.k_cache, st.v_cache, x, seq, pos, 1, w.l_ctx, out, ws)
+    st.dec.check_async(ws)
+    got = widen(bits_np(out))
+    assert np.all(np.isfinite(got))
+
+    def errors(a, b):
+        return (float(np.max(np.abs(a - b) / np.maximum(1.0, np.abs(b)))),
+                float(np.linalg.norm(a - b) / np.linalg.norm(b)))
+
+    scaled, rel = errors(got[:first], widen(oracle.f64_to_bf16_bits(x64)))
+    print(f"[prefill 62b] first {first} new tokens against the oracle: scaled-max {scaled:.3e} rel-L2 {rel:.3e}",
+          flush=True)
+    assert scaled <= MAX_SCALED and rel <= REL_L2
+    k_full, v_full = st.export_kv(0), st.export_kv(w.n_layers - 1)
+    # the same last token as a decode step after prefilling the tokens before it
+    st.k_cache.copy_(k_start)
+    st.v_cache.copy_(v_start)
+    out2 = torch.empty(N - 1, w.d_model, dtype=torch.bfloat16, device="cuda")
+    st.dec.prefill(st.packed, st.k_cache, st.v_cache, x[:N - 1].contiguous(), seq[:N - 1].contiguous(),
+                   pos[:N - 1].contiguous(), 1, w.l_ctx, out2, ws)
+    assert torch.equal(out2[:N - 256].view(torch.int16), out[:N - 256].view(torch.int16))  # whole chunks: same bits
+    st.x_in.copy_(x[N - 1:N])
+    st.positions.fill_(P0 + N - 1)
+    last = st.step()
+    st.dec.check_async(st.workspace)
+    scaled, rel = errors(widen(bits_np(last)), got[N - 1:N])
+    print(f"[prefill 62b] last token: decode step against its prefill row: scaled-max {scaled:.3e} rel-L2 {rel:.3e}",
+          flush=True)
+    assert scaled <= MAX_SCALED and rel <= REL_L2
+    T = P0 + N - 1
+    for (ka, va), layer in ((k_full, 0), (v_full, w.n_layers - 1)):
+        kb, vb = st.export_kv(layer)
+        for a, b in ((ka, kb), (va, vb)):
+            assert torch.equal(a[:, :P0].view(torch.int16), b[:, :P0].view(torch.int16))  # the prefix is untouched
+            da, db = widen(bits_np(a[:, P0:T + 1])), widen(bits_np(b[:, P0:T + 1]))
+            assert np.all(np.isfinite(da)) and np.all(np.isfinite(db))
+            assert np.max(np.abs(da - db) / np.maximum(1.0, np.abs(db))) <= MAX_SCALED
+    del st
+    gc.collect()
+    torch.cuda.empty_cache()
