@@ -371,27 +371,42 @@ __global__ __launch_bounds__(RL_THREADS) void residual_ln_kernel(
     const size_t stride = (size_t)pl.rows * d, rowoff = (size_t)b * d;
     f32x4 xn[NQ];
     float sum = 0.f;
+    // Slot sums of this thread's NQ column groups.  The slots of a group are added in index
+    // order; the loads of all groups go out together, eight in flight per thread per round trip
+    // (a slot index past a group's last one re-reads its last slot and is not added).
+    constexpr int BATCH = 8 / NQ;
+    int ns[NQ], ns_max = 0;
 #pragma unroll
     for (int i = 0; i < NQ; i++) {
         const int c = (i * RL_THREADS + tid) * 4;
+        ns[i] = c < d ? pl.nseg[c / pl.tile_cols] : 0;  // 4 columns share a tile
+        ns_max = ns[i] > ns_max ? ns[i] : ns_max;
         xn[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
-        if (c < d) {
-            const int ns = pl.nseg[c / pl.tile_cols];  // 4 columns share a tile
-            // slots are added in index order; four loads are in flight at a time (a slot index
-            // past the last one re-reads the last slot and is not added)
-            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-            for (int s0 = 0; s0 < ns; s0 += 4) {
-                f32x4 pv[4];
+    }
+    for (int s0 = 0; s0 < ns_max; s0 += BATCH) {
+        f32x4 pv[NQ][BATCH];
 #pragma unroll
-                for (int k = 0; k < 4; k++) {
-                    const int sk = s0 + k < ns ? s0 + k : ns - 1;
-                    pv[k] = *reinterpret_cast<const f32x4*>(part + (size_t)sk * stride + rowoff + c);
-                }
+        for (int i = 0; i < NQ; i++) {
+            const int c = (i * RL_THREADS + tid) * 4;
 #pragma unroll
-                for (int k = 0; k < 4; k++)
-                    if (s0 + k < ns) acc += pv[k];
+            for (int k = 0; k < BATCH; k++) {
+                int sk = s0 + k < ns[i] ? s0 + k : ns[i] - 1;
+                sk = sk < 0 ? 0 : sk;
+                pv[i][k] = c < d ? *reinterpret_cast<const f32x4*>(part + (size_t)sk * stride + rowoff + c)
+                                 : (f32x4){0.f, 0.f, 0.f, 0.f};
             }
-            f32x4 v = *reinterpret_cast<const f32x4*>(scale + c) * acc;
+        }
+#pragma unroll
+        for (int i = 0; i < NQ; i++)
+#pragma unroll
+            for (int k = 0; k < BATCH; k++)
+                if (s0 + k < ns[i]) xn[i] += pv[i][k];
+    }
+#pragma unroll
+    for (int i = 0; i < NQ; i++) {
+        const int c = (i * RL_THREADS + tid) * 4;
+        if (c < d) {
+            f32x4 v = *reinterpret_cast<const f32x4*>(scale + c) * xn[i];
             if (add_residual) v += *reinterpret_cast<const f32x4*>(xres + rowoff + c);
             *reinterpret_cast<f32x4*>(xres + rowoff + c) = v;
             xn[i] = v;
