@@ -116,11 +116,11 @@ struct GemmPlans {
 // workgroups that stream the same weight range (same x, different row group) are a
 // multiple of 8 apart in launch order, i.e. on the same XCD, where all but the first find
 // the weights in that XCD's L2.
-int auto_workgroups(int B, int K, int N, int c_split, int blk0, int blk1) {
+int auto_workgroups(int B, int K, int N, int c_split, int blk0, int blk1, int tile_cols = 0) {
     const int row_groups = B > 32 ? (B + 63) / 64 : 1;
     int g_max = PD_GEMM_WORKGROUPS / row_groups;
     if (row_groups > 1) g_max = g_max / 8 * 8;
-    return pd::qgemm_auto_workgroups(B, K, N, g_max, c_split, blk0, blk1);
+    return pd::qgemm_auto_workgroups(B, K, N, g_max, c_split, blk0, blk1, tile_cols);
 }
 
 GemmPlans gemm_plans(const Shape& s, int B, int g_in_opt, int g_out_opt) {
@@ -132,10 +132,11 @@ GemmPlans gemm_plans(const Shape& s, int B, int g_in_opt, int g_out_opt) {
     const int blk_ln = c_in < 1024 ? c_in : 1024;
     p.blk_o = c_attn < 16 ? c_attn : 16;
     p.blk_a = c_ffn < 16 ? c_ffn : 16;
-    const int g_in = g_in_opt > 0 ? g_in_opt : auto_workgroups(B, s.d, s.n_in, 0, 1, blk_ln);
-    const int g_out = g_out_opt > 0 ? g_out_opt : auto_workgroups(B, s.k_out, s.d, c_attn, p.blk_o, p.blk_a);
-    p.in = pd::qgemm_plan(B, s.d, s.n_in, g_in, 0, 1, blk_ln, &p.slots_in);
-    p.out = pd::qgemm_plan(B, s.k_out, s.d, g_out, c_attn, p.blk_o, p.blk_a, &p.slots_out);
+    const int tc = s.w16 ? PD_WGEMM_TILE_COLS : 0;
+    const int g_in = g_in_opt > 0 ? g_in_opt : auto_workgroups(B, s.d, s.n_in, 0, 1, blk_ln, tc);
+    const int g_out = g_out_opt > 0 ? g_out_opt : auto_workgroups(B, s.k_out, s.d, c_attn, p.blk_o, p.blk_a, tc);
+    p.in = pd::qgemm_plan(B, s.d, s.n_in, g_in, 0, 1, blk_ln, &p.slots_in, tc);
+    p.out = pd::qgemm_plan(B, s.k_out, s.d, g_out, c_attn, p.blk_o, p.blk_a, &p.slots_out, tc);
     return p;
 }
 
@@ -661,10 +662,11 @@ struct QgemmWs {
     pd::SkqPlan pl;
     size_t part, qa, qs, nseg, total;
 };
-QgemmWs qgemm_ws(int B, int K, int N, int workgroups) {
+QgemmWs qgemm_ws(int B, int K, int N, int workgroups, int tile_cols = 0) {
     QgemmWs q;
     int slots = 1;
-    q.pl = pd::qgemm_plan(B, K, N, workgroups > 0 ? workgroups : auto_workgroups(B, K, N, 0, 1, 1), 0, 1, 1, &slots);
+    q.pl = pd::qgemm_plan(B, K, N, workgroups > 0 ? workgroups : auto_workgroups(B, K, N, 0, 1, 1, tile_cols), 0, 1, 1,
+                          &slots, tile_cols);
     size_t o = 0;
     q.part = o; o += align256((size_t)slots * q.pl.rows * N * 4);
     q.qa = o; o += align256((size_t)B * K * 3);
@@ -679,7 +681,9 @@ pd_status pd_qgemm_workspace_bytes(int32_t B, int32_t K, int32_t N, int32_t work
     if (!bytes) return fail(PD_ERR_NULL, "bytes is NULL");
     if (B < 1 || B > 256 || K < 128 || K % 128 || N < 32 || N % 32) return fail(PD_ERR_SHAPE, "unsupported GEMM shape");
     if (workgroups < 0 || workgroups > 4096) return fail(PD_ERR_RANGE, "workgroups out of range");
-    *bytes = qgemm_ws(B, K, N, workgroups).total;
+    // one size for both test entries (the bf16-weight kernel's wider tiles have more slots)
+    const size_t a = qgemm_ws(B, K, N, workgroups).total, b = qgemm_ws(B, K, N, workgroups, PD_WGEMM_TILE_COLS).total;
+    *bytes = a > b ? a : b;
     return PD_OK;
 }
 
@@ -753,7 +757,7 @@ pd_status pd_wgemm_bf16(const void* packed_w, const uint16_t* a, int32_t B, int3
     if (workspace_bytes < need) return fail(PD_ERR_WORKSPACE, "workspace too small");
     if (!aligned(packed_w, 256) || !aligned(workspace, 256) || !aligned(a, 16) || !aligned(out, 16))
         return fail(PD_ERR_ALIGN, "misaligned device pointer");
-    QgemmWs q = qgemm_ws(B, K, N, workgroups);
+    QgemmWs q = qgemm_ws(B, K, N, workgroups, PD_WGEMM_TILE_COLS);
     hipStream_t st = static_cast<hipStream_t>(stream);
     unsigned char* wsb = static_cast<unsigned char*>(workspace);
     float* part = reinterpret_cast<float*>(wsb + q.part);

@@ -11,9 +11,10 @@ namespace pd {
 
 // ---- qgemm.hip
 void qgemm_config(int B, int* bm, int* ns, int* tile_cols);
+// tile_cols = 0: the int8 kernel's tile width; PD_WGEMM_TILE_COLS for the bf16-weight kernel
 SkqPlan qgemm_plan(int B, int K, int N, int workgroups, int c_split, int blk0, int blk1,
-                   int* max_slots);
-int qgemm_auto_workgroups(int B, int K, int N, int g_max, int c_split, int blk0, int blk1);
+                   int* max_slots, int tile_cols = 0);
+int qgemm_auto_workgroups(int B, int K, int N, int g_max, int c_split, int blk0, int blk1, int tile_cols = 0);
 hipError_t launch_skq_table(SkqPlan pl, int* nseg, hipStream_t stream);
 hipError_t launch_qgemm(const void* wp, const void* qa, const float* scale_t, float* part, int B,
                         int K, int N, SkqPlan pl, int nd, hipStream_t stream);
@@ -26,7 +27,9 @@ hipError_t launch_pack_vector(const uint16_t* src, float* dst, int N, int mode, 
 hipError_t launch_qgemm_reduce(const float* part, const float* scale, float* out, int B, int N,
                                SkqPlan pl, hipStream_t stream);
 
-// ---- wgemm.hip: the same product with bf16 weights (same plan, same partial slots)
+// ---- wgemm.hip: the same product with bf16 weights (same kind of plan with tiles of
+// PD_WGEMM_TILE_COLS columns, same partial slots)
+#define PD_WGEMM_TILE_COLS 512
 hipError_t launch_wgemm_bf16(const void* wp, const void* qa, const float* scale_t, float* part, int B,
                              int K, int N, SkqPlan pl, int nd, hipStream_t stream);
 hipError_t launch_pack_matrix_bf16(const uint16_t* w, void* dst, int K, int N, int mode, int n_qkv, int F,

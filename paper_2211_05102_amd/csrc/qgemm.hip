@@ -616,9 +616,10 @@ void qgemm_config(int B, int* bm, int* ns, int* tile_cols) {
 // Plan of a [K][N] projection for batch B: `workgroups` share the matrix (capped by
 // the number of units); returns the largest number of segments in any tile.
 SkqPlan qgemm_plan(int B, int K, int N, int workgroups, int c_split, int blk0, int blk1,
-                   int* max_slots) {
+                   int* max_slots, int tile_cols) {
     int bm, ns, tc;
     qgemm_config(B, &bm, &ns, &tc);
+    if (tile_cols > 0) tc = tile_cols;  // (the bf16-weight kernel's tiles are wider)
     SkqPlan pl;
     pl.tile_cols = tc;
     pl.C = K / 128;
@@ -653,12 +654,12 @@ SkqPlan qgemm_plan(int B, int K, int N, int workgroups, int c_split, int blk0, i
 // share the bandwidth; a few idle compute units cost less than one ring of extra units on
 // the slowest workgroup (62B-shaped input projection: 232 ranges of 80 units beat 256 of
 // 72 or 74).
-int qgemm_auto_workgroups(int B, int K, int N, int g_max, int c_split, int blk0, int blk1) {
+int qgemm_auto_workgroups(int B, int K, int N, int g_max, int c_split, int blk0, int blk1, int tile_cols) {
     if (g_max < 16) return g_max < 1 ? 1 : g_max;
     int best_g = g_max;
     long long best_cost = -1;
     for (int g = g_max; g >= g_max - g_max / 8; g -= 8) {
-        const SkqPlan pl = qgemm_plan(B, K, N, g, c_split, blk0, blk1, nullptr);
+        const SkqPlan pl = qgemm_plan(B, K, N, g, c_split, blk0, blk1, nullptr, tile_cols);
         const long long U = (long long)pl.T * pl.C;
         long long longest = 0;
         for (int i = 0; i < pl.G; i++) {

@@ -22,9 +22,10 @@
 // Weights are pre-tiled so that a wavefront's 16-byte-per-lane load is 1 KiB
 // contiguous and already a B operand:
 //   packed[(st*(K/16) + kb)*64 + lane] holds W[kb*16 + (lane/32)*8 + 0..7][st*32 + lane%32].
-// 8 wavefronts per workgroup, one 32-column subtile each, two per SIMD; each keeps R
-// units (8 KiB each) of its weight stream in flight in registers.  The digit planes go
-// global -> registers -> (conversion) -> one of two LDS stages shared by the 8 waves.
+// 8 wavefronts per workgroup, two 32-column subtiles each (512-column tiles), two per SIMD;
+// each keeps one unit (16 KiB) of its weight stream in flight in registers.  The digit
+// planes go global -> registers -> (conversion) -> one of two LDS stages shared by the
+// 8 waves.
 #include "common.h"
 #include "kernels.h"
 
@@ -63,24 +64,28 @@ __device__ __forceinline__ void digits_to_bf16_planes(const u32x2 (&dg)[ND], flo
     }
 }
 
-// BM: 32-row batch blocks; ND: digit planes in = bf16 planes fed to the matrix pipe;
-// R: weight units per wave in the register ring.  grid = (G workgroups, row groups of
-// 32*BM rows).
-template <int BM, int ND, int R, int WAUX>
+// BM: 32-row batch blocks; ND: digit planes in = bf16 planes fed to the matrix pipe.
+// grid = (G workgroups, row groups of 32*BM rows).  Each wavefront owns NS = 2 adjacent
+// 32-column subtiles of a 512-column tile (an operand read from LDS feeds two MFMAs) and
+// keeps one unit of its weight stream (16 KiB) in registers as a rolling buffer: a 1 KiB
+// piece is requested again, for the next unit, as soon as its last MFMA has been issued.
+template <int BM, int ND, int WAUX>
 __global__ __launch_bounds__(WNT) void wgemm_bf16_kernel(const uint4* __restrict__ wp,
                                                           const unsigned char* __restrict__ qa,
                                                           const float* __restrict__ scale_t,
                                                           float* __restrict__ part, int B, int K, int N,
                                                           SkqPlan pl) {
     constexpr int KC = QCHUNK;                 // k-extent of one unit = one LDS stage
+    constexpr int NS = 2;                      // 32-column subtiles per wave
     constexpr int ROWS = BM * 32;
     constexpr int PITCH = ND * KC * 2 + 16;    // bytes per row: ND bf16 planes; +16 spreads rows over banks
     constexpr int PPR = KC / 8;                // 8-element pieces per row
     constexpr int NPIECE = ROWS * PPR;
     constexpr int APT = NPIECE / WNT;          // pieces per thread per stage
-    constexpr int KB = KC / 16;                // 16-k blocks (1 KiB per wave each) per unit
-    constexpr int TSUB = WNT / 64;             // one 32-column subtile per wave
+    constexpr int KB = KC / 16;                // 16-k blocks (1 KiB per wave and subtile each) per unit
+    constexpr int TSUB = (WNT / 64) * NS;      // 32-column subtiles per tile
     constexpr int STAGE = ROWS * PITCH;
+    static_assert(TSUB * 32 == PD_WGEMM_TILE_COLS, "the plan's tiles are this kernel's tiles");
     static_assert(NPIECE % WNT == 0 && APT >= 1, "pieces divide over the threads");
     static_assert(2 * STAGE <= 160 * 1024, "LDS");
     __shared__ __attribute__((aligned(16))) unsigned char lds[2][STAGE];
@@ -115,15 +120,18 @@ __global__ __launch_bounds__(WNT) void wgemm_bf16_kernel(const uint4* __restrict
     // (tile, chunk) of the next weight unit to fetch and chunk of the next activation stage to
     // load; both saturate at the last unit of the range (fetching it again is an L2 hit)
     int u_w = u0, t_w = t_cur, c_w = c_cur, u_a = u0, c_a = c_cur;
+    uint32_t wo[NS];  // byte offsets of the unit's two 8 KiB pieces in the packed matrix
     auto w_next = [&]() {
-        int st = t_w * TSUB + wave;
-        st = st < n_sub ? st : n_sub - 1;  // ragged last tile: result dropped at the store
-        const uint32_t off = (uint32_t)st * (uint32_t)(K * 64) + (uint32_t)c_w * (uint32_t)(KC * 64);
+#pragma unroll
+        for (int i = 0; i < NS; i++) {
+            int st = t_w * TSUB + wave * NS + i;
+            st = st < n_sub ? st : n_sub - 1;  // ragged last tile: result dropped at the store
+            wo[i] = (uint32_t)st * (uint32_t)(K * 64) + (uint32_t)c_w * (uint32_t)(KC * 64);
+        }
         if (u_w < u1 - 1) {
             u_w++;
             if (++c_w == C) { c_w = 0; t_w++; }
         }
-        return off;
     };
     auto a_next = [&]() {
         const int c = c_a;
@@ -145,21 +153,17 @@ __global__ __launch_bounds__(WNT) void wgemm_bf16_kernel(const uint4* __restrict
         soff[it] = rg * 4;
     }
 
-    u32x4 ring[R][KB];
+    u32x4 ring[NS][KB];
     u32x2 areg[APT][ND];
     float sreg[APT];
-    f32x16 acc[BM];
+    f32x16 acc[BM][NS];
 #pragma unroll
     for (int bm = 0; bm < BM; bm++)
 #pragma unroll
-        for (int r = 0; r < 16; r++) acc[bm][r] = 0.f;
+        for (int i = 0; i < NS; i++)
+#pragma unroll
+            for (int r = 0; r < 16; r++) acc[bm][i][r] = 0.f;
 
-#define W_FETCH(s)                                                                       \
-    {                                                                                    \
-        const uint32_t o_ = w_next();                                                    \
-        _Pragma("unroll") for (int kb = 0; kb < KB; kb++)                                \
-            ring[s][kb] = __builtin_amdgcn_raw_buffer_load_b128(w_rs, lane16 + kb * 1024, o_, WAUX); \
-    }
     // digits and scales of the next activation chunk -> registers
 #define W_ALOAD()                                                                        \
     {                                                                                    \
@@ -180,105 +184,77 @@ __global__ __launch_bounds__(WNT) void wgemm_bf16_kernel(const uint4* __restrict
                 *reinterpret_cast<u32x4*>(&lds[buf][aslot[it] + p * (KC * 2)]) = pl_[p]; \
         }                                                                                \
     }
-    // One unit: stage `cur` against ring slot s.  First the next unit's stage is written and
-    // the digits of the unit after that are requested; each 1 KiB piece of the ring slot is
-    // refilled as soon as its last MFMA has been issued.
-#define W_STEP(s)                                                                        \
-    {                                                                                    \
-        W_ASTORE(cur ^ 1)                                                                \
-        W_ALOAD()                                                                        \
-        const uint32_t wo_ = w_next();                                                   \
-        __builtin_amdgcn_sched_barrier(0);                                               \
-        _Pragma("unroll") for (int kb = 0; kb < KB; kb++) {                              \
-            const bf16x8 b_ = __builtin_bit_cast(bf16x8, ring[s][kb]);                   \
-            _Pragma("unroll") for (int p = 0; p < ND; p++) {                             \
-                _Pragma("unroll") for (int bm = 0; bm < BM; bm++) {                      \
-                    const bf16x8 a_ = *reinterpret_cast<const bf16x8*>(                  \
-                        &lds[cur][(bm * 32 + l32) * PITCH + p * (KC * 2) + kb * 32 + g * 16]); \
-                    acc[bm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_, b_, acc[bm], 0, 0, 0); \
-                }                                                                        \
-            }                                                                            \
-            ring[s][kb] = __builtin_amdgcn_raw_buffer_load_b128(w_rs, lane16 + kb * 1024, wo_, WAUX); \
-            __builtin_amdgcn_sched_barrier(0);                                           \
-        }                                                                                \
-        lds_barrier();                                                                   \
-        cur ^= 1;                                                                        \
-        u++;                                                                             \
-    }
 
-    int u = u0, cur = 0;
-    // The part of a tile inside this range is done: store its fp32 sums as this range's
-    // partial of the tile.  D layout of the 32x32 MFMA: register r of lane (l32, g) is row
-    // 8*(r/4) + 4*g + r%4, column l32.
-    auto end_tile_part = [&](int n_units) {
-        c_cur += n_units;
-        const int st = t_cur * TSUB + wave;
-        if (st < n_sub) {
+    // fill: the first unit's weights, its activation stage, the digits of the second unit
+    W_ALOAD()
+    w_next();
+#pragma unroll
+    for (int kb = 0; kb < KB; kb++)
+#pragma unroll
+        for (int i = 0; i < NS; i++)
+            ring[i][kb] = __builtin_amdgcn_raw_buffer_load_b128(w_rs, lane16 + kb * 1024, wo[i], WAUX);
+    W_ASTORE(0)
+    W_ALOAD()
+    // Everything requested so far is waited for here, once: the compiler derives the wait at
+    // the head of the unit loop from all paths that reach it, and merged with this path it
+    // would otherwise drain the weight buffer on every turn.
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+    lds_barrier();
+
+    int cur = 0;
+    for (int u = u0; u < u1; u++) {
+        // One unit: stage `cur` against the weight buffer.  First the next unit's stage is
+        // written and the digits of the unit after that are requested.
+        W_ASTORE(cur ^ 1)
+        W_ALOAD()
+        w_next();  // wo[]: where the next unit's pieces are
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int kb = 0; kb < KB; kb++) {
+            const bf16x8 b0 = __builtin_bit_cast(bf16x8, ring[0][kb]);
+            const bf16x8 b1 = __builtin_bit_cast(bf16x8, ring[1][kb]);
+#pragma unroll
+            for (int p = 0; p < ND; p++) {
+#pragma unroll
+                for (int bm = 0; bm < BM; bm++) {
+                    const bf16x8 a_ = *reinterpret_cast<const bf16x8*>(
+                        &lds[cur][(bm * 32 + l32) * PITCH + p * (KC * 2) + kb * 32 + g * 16]);
+                    acc[bm][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_, b0, acc[bm][0], 0, 0, 0);
+                    acc[bm][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_, b1, acc[bm][1], 0, 0, 0);
+                }
+            }
+            ring[0][kb] = __builtin_amdgcn_raw_buffer_load_b128(w_rs, lane16 + kb * 1024, wo[0], WAUX);
+            ring[1][kb] = __builtin_amdgcn_raw_buffer_load_b128(w_rs, lane16 + kb * 1024, wo[1], WAUX);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        lds_barrier();
+        cur ^= 1;
+        // The part of a tile inside this range is done: store its fp32 sums as this range's
+        // partial of the tile.  D layout of the 32x32 MFMA: register r of lane (l32, g) is row
+        // 8*(r/4) + 4*g + r%4, column l32.
+        if (++c_cur == C || u + 1 == u1) {
             const uint32_t rowb = (uint32_t)N * 4u;
 #pragma unroll
-            for (int bm = 0; bm < BM; bm++)
+            for (int i = 0; i < NS; i++) {
+                const int st = t_cur * TSUB + wave * NS + i;
 #pragma unroll
-                for (int r = 0; r < 16; r++) {
-                    const uint32_t row = (uint32_t)(slot * pl.rows + row0 + bm * 32 + 8 * (r >> 2) + 4 * g + (r & 3));
-                    const float f_ = acc[bm][r];  // (a bit cast of a vector element lvalue reads element 0)
-                    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, f_), p_rs,
-                                                          row * rowb + (uint32_t)(st * 128 + l32 * 4), 0,
-                                                          PD_WRITE_THROUGH);
-                }
-        }
+                for (int bm = 0; bm < BM; bm++)
 #pragma unroll
-        for (int bm = 0; bm < BM; bm++)
-#pragma unroll
-            for (int r = 0; r < 16; r++) acc[bm][r] = 0.f;
-        if (c_cur == C) { c_cur = 0; t_cur++; slot = 0; }
-    };
-    // Outer loop: (re)start the pipeline at ring slot 0.  Inner loop: the tile parts that run
-    // on it; a part that is not a whole number of turns of the ring leaves the ring out of
-    // phase and falls out to a restart.
-    for (;;) {
-        u_w = u_a = u;
-        t_w = t_cur;
-        c_w = c_a = c_cur;
-        W_ALOAD()
-#pragma unroll
-        for (int s = 0; s < R; s++) W_FETCH(s)
-        W_ASTORE(0)
-        W_ALOAD()
-        // Everything requested so far is waited for here, once: the compiler derives the wait
-        // at the head of the unit loop from all paths that reach it, and merged with this path
-        // it would otherwise drain the ring on every turn.
-        __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
-        lds_barrier();
-        cur = 0;
-        bool restart = false;
-        while (!restart) {
-            const int rest = u1 - u;
-            const int n_units = C - c_cur < rest ? C - c_cur : rest;
-            for (int turns = n_units / R; turns > 0; --turns) {
-#pragma unroll
-                for (int s = 0; s < R; s++) W_STEP(s)
+                    for (int r = 0; r < 16; r++) {
+                        const uint32_t row = (uint32_t)(slot * pl.rows + row0 + bm * 32 + 8 * (r >> 2) + 4 * g + (r & 3));
+                        const float f_ = acc[bm][i][r];  // (a bit cast of a vector element lvalue reads element 0)
+                        if (st < n_sub)
+                            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, f_), p_rs,
+                                                                  row * rowb + (uint32_t)(st * 128 + l32 * 4), 0,
+                                                                  PD_WRITE_THROUGH);
+                        acc[bm][i][r] = 0.f;
+                    }
             }
-            const int rem = n_units % R;
-            if (rem > 0) {
-                W_STEP(0)
-                if (R > 2 && rem > 1) {
-                    W_STEP(1 % R)
-                    if (rem > 2) { W_STEP(2 % R) }
-                }
-                __builtin_amdgcn_s_waitcnt(0x0F70);  // nothing of these steps stays in flight
-                end_tile_part(n_units);
-                if (u == u1) return;
-                restart = true;
-            } else {
-                end_tile_part(n_units);
-                if (u == u1) return;
-            }
+            if (c_cur == C) { c_cur = 0; t_cur++; slot = 0; }
         }
     }
-#undef W_FETCH
 #undef W_ALOAD
 #undef W_ASTORE
-#undef W_STEP
 }
 
 // canonical bf16 [K][N] -> the packed operand order above, columns through the same
@@ -313,7 +289,7 @@ hipError_t launch_wgemm_bf16(const void* wp, const void* qa, const float* scale_
                              int K, int N, SkqPlan pl, int nd, hipStream_t stream) {
     int bm, ns, tc;
     qgemm_config(B, &bm, &ns, &tc);
-    if (tc != (WNT / 64) * 32) return hipErrorInvalidValue;  // the plan's tiles are this kernel's tiles
+    if (pl.tile_cols != PD_WGEMM_TILE_COLS) return hipErrorInvalidValue;  // the plan's tiles are this kernel's tiles
     dim3 grid(pl.G, (B + 32 * bm - 1) / (32 * bm)), block(WNT);
     const uint4* w4 = reinterpret_cast<const uint4*>(wp);
     const unsigned char* q = reinterpret_cast<const unsigned char*>(qa);
@@ -325,9 +301,9 @@ hipError_t launch_wgemm_bf16(const void* wp, const void* qa, const float* scale_
 #define PD_LAUNCH(BMv, WAUXv)                                                                          \
     do {                                                                                               \
         if (nd == 3)                                                                                   \
-            wgemm_bf16_kernel<BMv, 3, 2, WAUXv><<<grid, block, 0, stream>>>(w4, q, scale_t, part, B, K, N, pl); \
+            wgemm_bf16_kernel<BMv, 3, WAUXv><<<grid, block, 0, stream>>>(w4, q, scale_t, part, B, K, N, pl); \
         else                                                                                           \
-            wgemm_bf16_kernel<BMv, 2, 2, WAUXv><<<grid, block, 0, stream>>>(w4, q, scale_t, part, B, K, N, pl); \
+            wgemm_bf16_kernel<BMv, 2, WAUXv><<<grid, block, 0, stream>>>(w4, q, scale_t, part, B, K, N, pl); \
     } while (0)
     if (bm == 1) PD_LAUNCH(1, 2);
     else if (grid.y > 1) PD_LAUNCH(2, 0);  // several row groups read the weights: leave them cacheable
